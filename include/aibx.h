@@ -1,0 +1,200 @@
+/*
+ * aibx - GPU hot path of a distributed KV cache with prefix-aware routing (MI355X / gfx950).
+ *
+ * The paper (AIBrix, arXiv 2504.03648) describes a KV cache pool shared across inference
+ * engines (Section 3.2.5, "Distributed KV Cache Pool") and a gateway policy that routes a
+ * request to the instance holding a reusable prefix of its KV cache (Section 3.2.2, the
+ * "prefix-cache-aware" policy). This library implements the data-parallel work behind both:
+ *
+ *   aibx_block_hash    chained per-block hashes of request token streams
+ *   aibx_prefix_match  lookup of those hashes in a GPU-resident cache index + first-miss length
+ *   aibx_index_insert  metadata update: (key -> value) upsert           (Section 3.2.5)
+ *   aibx_index_evict   metadata update: removal of evicted keys          (Section 3.2.5)
+ *   aibx_kv_gather     paged KV pool -> contiguous staging (offload)     (Section 3.2.5)
+ *   aibx_kv_scatter    contiguous staging -> paged KV pool (onload)      (Section 3.2.5)
+ *
+ * The paper prints no hash function, index layout or copy layout; the rules stated below are
+ * this library's own and are what its results are checked against.
+ *
+ * General conventions
+ *   - Every pointer named d_* is DEVICE memory owned by the caller. The library allocates no
+ *     device memory; the only allocation it makes is the small host handle of an index.
+ *     Pointers without the d_ prefix (descriptors, out-parameters) are HOST memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream). Every call only
+ *     enqueues work on that stream and returns; it never synchronises. Calls that touch the
+ *     same index, pool pages or staging slots must be ordered by the caller (same stream, or
+ *     events). Concurrent gather/scatter calls are safe iff their destination bytes are disjoint
+ *     and no call reads what another writes.
+ *   - Return value: AIBX_OK (0) or a negative aibx_status. Conditions only the device can see
+ *     (table full, page id out of range, key absent) are counted in caller-provided device
+ *     counters, not raised.
+ *   - A count of zero (n = 0, n_req = 0) is a valid no-op and returns AIBX_OK.
+ */
+#ifndef AIBX_H_
+#define AIBX_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  AIBX_OK = 0,
+  AIBX_ERR_INVALID_ARG = -1, /* null pointer, negative count, value out of its stated range   */
+  AIBX_ERR_ALIGN = -2,       /* a pointer, stride or size is not a multiple of what is stated */
+  AIBX_ERR_UNSUPPORTED = -3, /* e.g. n_slots not a power of two, or below the minimum         */
+  AIBX_ERR_HIP = -4          /* the HIP runtime refused a launch; see aibx_last_hip_error()   */
+} aibx_status;
+
+/* Value reported for a key that is not in the index. Never store it as a value. */
+#define AIBX_NO_VALUE 0xFFFFFFFFFFFFFFFFull
+/* The two key values the index reserves; aibx_block_hash never produces them. */
+#define AIBX_KEY_EMPTY 0x0000000000000000ull
+#define AIBX_KEY_TOMBSTONE 0xFFFFFFFFFFFFFFFFull
+
+/* Library version (major*10000 + minor*100 + patch) and the version of the hash definition;
+ * hashes are comparable only between equal hash versions. */
+int aibx_version(void);
+int aibx_hash_version(void);
+/* Static, human-readable text for a status code. */
+const char* aibx_strerror(int status);
+/* Text of the last HIP error seen by this thread inside the library ("" if none). */
+const char* aibx_last_hip_error(void);
+
+/* ------------------------------------------------------------------------------------------
+ * Chained per-block prefix hash.  (Token-pattern analysis for prefix-cache-aware routing,
+ * Section 3.2.2; detection of overlapping token sequences across requests, Section 3.2.5.)
+ *
+ * Requests are concatenated: request r owns d_tokens[d_tok_off[r] .. d_tok_off[r+1]) and
+ * d_hash_out[d_blk_off[r] .. d_blk_off[r+1]), where the caller has set
+ * d_blk_off[r+1]-d_blk_off[r] = floor(len_r / block_size): only full blocks are hashed.
+ * With all arithmetic on uint64 modulo 2^64 and
+ *   K0=0x9E3779B97F4A7C15 K1=0x6A09E667F3BCC909 K2=0xBB67AE8584CAA73B K3=0x3C6EF372FE94F82B
+ *   F(x): x^=x>>32; x*=K1; x^=x>>29; x*=K2; x^=x>>32
+ *   term(t,i) = y ^ (y>>32),  y = (zero_extend(uint32(t)) ^ K0*(i+1)) * K1
+ * block j of a request gets
+ *   c_j = sum_{i<block_size} term(tok[j*block_size+i], i)
+ *   s_j = K2*s_{j-1} + F(c_j),   s_{-1} = F(seed ^ K3)
+ *   h_j = F(s_j ^ K3), except that 0 and 2^64-1 are replaced by h_j ^ K0.
+ * h_j depends on `seed` and on the first (j+1)*block_size tokens of the request only, so two
+ * requests share h_0..h_{k-1} exactly when they share their first k blocks of tokens (up to
+ * 64-bit collisions). `seed` separates key spaces (model, adapter, tenant).
+ *
+ *   d_tokens   int32[d_tok_off[n_req]]   token ids (bit patterns; negative ids are allowed)
+ *   d_tok_off  int64[n_req+1]            non-decreasing, d_tok_off[0] >= 0
+ *   d_blk_off  int64[n_req+1]            d_blk_off[0] = 0, d_blk_off[n_req] = n_blocks_total
+ *   block_size in [1, 1024]
+ *   d_hash_out uint64[n_blocks_total]    written
+ * The offsets are trusted (they are device data); n_blocks_total must equal d_blk_off[n_req].
+ * Pointers must be aligned to their element size. Errors: INVALID_ARG, ALIGN, HIP.
+ */
+int aibx_block_hash(const int32_t* d_tokens, const int64_t* d_tok_off, const int64_t* d_blk_off,
+                    int32_t n_req, int64_t n_blocks_total, int32_t block_size, uint64_t seed,
+                    uint64_t* d_hash_out, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Cache index: a GPU-resident open-addressing table key -> value (the cache pool's metadata of
+ * Section 3.2.5: which blocks are cached and where). Keys are any uint64 except the two
+ * reserved values; values are any uint64 except AIBX_NO_VALUE. Observable behaviour is that of
+ * a map with capacity n_slots; where a key sits in the table is not observable.
+ */
+typedef struct aibx_index aibx_index_t; /* opaque host handle */
+
+/* Bytes of device storage a table of n_slots needs. n_slots: power of two, 8 <= n_slots <= 2^36.
+ * Errors: INVALID_ARG (null out), UNSUPPORTED. */
+int aibx_index_storage_bytes(uint64_t n_slots, size_t* out_bytes);
+
+/* Binds a handle to caller-owned storage (256-byte aligned, >= aibx_index_storage_bytes) and
+ * enqueues a clear. The storage must outlive the handle. Errors: INVALID_ARG, ALIGN,
+ * UNSUPPORTED, HIP. */
+int aibx_index_create(void* d_storage, size_t bytes, uint64_t n_slots, void* stream,
+                      aibx_index_t** out);
+/* Frees the host handle only (never the device storage). NULL is accepted. */
+int aibx_index_destroy(aibx_index_t* index);
+/* Enqueues removal of every key. */
+int aibx_index_clear(aibx_index_t* index, void* stream);
+
+/* Batch upsert ("metadata update", Section 3.2.5). For each i < n: key absent -> stored with
+ * d_values[i] (inserted); key present -> its value is overwritten (updated). A reserved key, or
+ * a new key when no slot is free, is dropped (full). The same key may appear several times in one
+ * batch if its values are identical: it then counts once as inserted (or updated) and the other
+ * occurrences as updated; with differing values one of them wins.
+ *   d_counters3 uint64[3], nullable: {inserted, updated, full} are ADDED to it.
+ * Errors: INVALID_ARG, ALIGN (8-byte), HIP. */
+int aibx_index_insert(aibx_index_t* index, const uint64_t* d_keys, const uint64_t* d_values,
+                      int64_t n, uint64_t* d_counters3, void* stream);
+
+/* Batch removal of evicted keys (Section 3.2.5 names eviction; choosing the victims is the
+ * caller's policy). For each i < n: key present -> removed, d_values_out[i] = its value
+ * (evicted); absent or reserved -> d_values_out[i] = AIBX_NO_VALUE (missing). If a key appears
+ * several times in one batch exactly one occurrence reports the value.
+ *   d_values_out uint64[n], nullable;  d_counters2 uint64[2], nullable: {evicted, missing} ADDED.
+ * Errors: INVALID_ARG, ALIGN, HIP. */
+int aibx_index_evict(aibx_index_t* index, const uint64_t* d_keys, int64_t n,
+                     uint64_t* d_values_out, uint64_t* d_counters2, void* stream);
+
+/* *d_live_out (device uint64) = number of keys in the index. */
+int aibx_index_count(const aibx_index_t* index, uint64_t* d_live_out, void* stream);
+
+/* Writes the live (key, value) pairs, in no particular order, to d_keys_out/d_values_out (each
+ * uint64[capacity]) and the number of live keys to *d_n_out (device uint64; the caller zeroes
+ * nothing - the call resets it). Pairs beyond `capacity` are counted but not written. */
+int aibx_index_dump(const aibx_index_t* index, uint64_t* d_keys_out, uint64_t* d_values_out,
+                    uint64_t capacity, uint64_t* d_n_out, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Prefix match.  (The "reusable prefix cache" test of the prefix-cache-aware policy,
+ * Section 3.2.2: the caller compares match_len / n_r with its threshold.)
+ * For every block b: d_values_out[b] = value of d_hashes[b] in the index, or AIBX_NO_VALUE.
+ * For every request r: d_match_len[r] = the smallest j with block d_blk_off[r]+j absent, or its
+ * block count if none is absent ("first miss": a block found behind a missing one still reports
+ * its value but does not extend the match).
+ *   d_hashes uint64[n_blocks_total]; d_blk_off int64[n_req+1] as for aibx_block_hash;
+ *   d_values_out uint64[n_blocks_total], nullable; d_match_len int32[n_req].
+ * Errors: INVALID_ARG, ALIGN, HIP. */
+int aibx_prefix_match(const aibx_index_t* index, const uint64_t* d_hashes,
+                      const int64_t* d_blk_off, int32_t n_req, int64_t n_blocks_total,
+                      uint64_t* d_values_out, int32_t* d_match_len, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Paged-KV gather / scatter.  (Moving KV blocks between the engine's paged memory and the
+ * cache's contiguous buffers: offload of blocks chosen to persist, onload of matched ones,
+ * Section 3.2.5.)  Pure byte copies - no conversion of any kind.
+ *
+ * The pool is n_seg planes; segment s of page p is the seg_bytes bytes at
+ *   base + s*seg_stride + p*page_stride.
+ * (n_seg = 1: page-major pool; n_seg = 2*layers: one plane per layer and K/V; n_seg = layers:
+ * latent-only pages.) A staging block holds the n_seg segments of one page back to back in
+ * plane order; block q starts at d_staging + q*staging_block_stride.
+ */
+typedef struct {
+  void* base;           /* DEVICE pointer, 16-byte aligned                           */
+  int32_t n_seg;        /* >= 1                                                      */
+  uint64_t seg_stride;  /* bytes between planes; multiple of 16                      */
+  uint64_t page_stride; /* bytes between pages of one plane; multiple of 16, >= seg_bytes */
+  uint64_t seg_bytes;   /* contiguous bytes per (plane, page); multiple of 16, > 0   */
+  int64_t n_pages;      /* >= 0                                                      */
+} aibx_pool_desc;
+
+/* Gather: for i < n, page p = d_page_ids[i], slot q = d_slot_ids ? d_slot_ids[i] : i:
+ *   staging block q <- page p.            Scatter: page p <- staging block q.
+ * p < 0 marks a hole: the entry is skipped. p >= n_pages: the entry is skipped and
+ * *d_bad_page_counter (device uint64, nullable) is incremented. Slot ids are trusted: the
+ * caller guarantees 0 <= q and (q+1)*staging_block_stride <= size of the staging buffer.
+ * Entries of one call must not share a destination (slot in gather, page in scatter).
+ *   pool (host struct, read during the call); d_page_ids int32[n]; d_slot_ids int32[n] or NULL;
+ *   d_staging 16-byte aligned; staging_block_stride multiple of 16, >= n_seg*seg_bytes.
+ * Errors: INVALID_ARG, ALIGN, HIP. */
+int aibx_kv_gather(const aibx_pool_desc* pool, const int32_t* d_page_ids,
+                   const int32_t* d_slot_ids, int64_t n, void* d_staging,
+                   uint64_t staging_block_stride, uint64_t* d_bad_page_counter, void* stream);
+int aibx_kv_scatter(const aibx_pool_desc* pool, const int32_t* d_page_ids,
+                    const int32_t* d_slot_ids, int64_t n, const void* d_staging,
+                    uint64_t staging_block_stride, uint64_t* d_bad_page_counter, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AIBX_H_ */

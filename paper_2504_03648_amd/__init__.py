@@ -1,0 +1,9 @@
+"""aibx: MI355X-native hot path of a distributed KV cache with prefix-aware routing
+(block hashing, prefix match against a GPU-resident index, index insert/evict, paged-KV
+gather/scatter). See include/aibx.h for the C ABI; `binding` mirrors it one to one."""
+from . import binding
+from .binding import (AibxError, PoolDesc, AIBX_NO_VALUE, aibx_version, aibx_hash_version,
+                      aibx_block_hash, aibx_index_storage_bytes, aibx_index_create,
+                      aibx_index_destroy, aibx_index_clear, aibx_index_insert, aibx_index_evict,
+                      aibx_index_count, aibx_index_dump, aibx_prefix_match, make_pool_desc,
+                      aibx_kv_gather, aibx_kv_scatter)

@@ -1,0 +1,30 @@
+// Shared host-side helpers of the aibx library (status codes, HIP error capture, argument checks).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "aibx.h"
+
+namespace aibx {
+
+typedef uint64_t u64;
+typedef uint32_t u32;
+
+constexpr int kWave = 64;  // CDNA wavefront width
+
+// Records the text of a failed HIP call for aibx_last_hip_error() and returns AIBX_ERR_HIP.
+int hip_failed(hipError_t e);
+
+// After a kernel launch: AIBX_OK, or AIBX_ERR_HIP with the error text recorded.
+inline int launch_status() {
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? AIBX_OK : hip_failed(e);
+}
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+inline hipStream_t as_stream(void* s) { return static_cast<hipStream_t>(s); }
+
+}  // namespace aibx

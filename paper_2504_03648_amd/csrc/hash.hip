@@ -1,0 +1,262 @@
+// Chained per-block prefix hash (the token-pattern analysis behind the paper's prefix-cache-aware
+// routing, Section 3.2.2, and its cross-request KV reuse, Section 3.2.5). The definition is in
+// aibx.h; this file evaluates it on the GPU.
+//
+// Layout of the work: one workgroup of kHashWaves wavefronts per request. A wavefront takes a
+// tile of 1024 consecutive tokens (64 coalesced tokens per load, 16 loads in flight), so a lane
+// always sees the same position-in-block and folds its position constant once. The per-block sums
+// are formed by a transposing butterfly across the lanes that share a block, the block digests
+// are scanned across lanes with the chain's affine step (s -> K2*s + d), and the carry between
+// tiles of one request goes through LDS.
+#include "common.h"
+
+namespace aibx {
+namespace {
+
+constexpr u64 K0 = 0x9E3779B97F4A7C15ull;
+constexpr u64 K1 = 0x6A09E667F3BCC909ull;
+constexpr u64 K2 = 0xBB67AE8584CAA73Bull;
+constexpr u64 K3 = 0x3C6EF372FE94F82Bull;
+
+constexpr int kHashWaves = 4;
+constexpr int kTileTokens = 1024;  // tokens per wavefront tile
+constexpr int kLoads = kTileTokens / kWave;
+
+__host__ __device__ constexpr u64 ipow(u64 base, u64 e) {
+  u64 r = 1;
+  while (e) {
+    if (e & 1) r *= base;
+    base *= base;
+    e >>= 1;
+  }
+  return r;
+}
+
+__device__ __forceinline__ u64 fin(u64 x) {
+  x ^= x >> 32;
+  x *= K1;
+  x ^= x >> 29;
+  x *= K2;
+  x ^= x >> 32;
+  return x;
+}
+
+__device__ __forceinline__ u64 out_hash(u64 s) {
+  u64 h = fin(s ^ K3);
+  return (h == 0ull || h == ~0ull) ? (h ^ K0) : h;
+}
+
+__device__ __forceinline__ u64 shfl_xor64(u64 v, int mask) {
+  u32 lo = (u32)v, hi = (u32)(v >> 32);
+  lo = __shfl_xor(lo, mask);
+  hi = __shfl_xor(hi, mask);
+  return ((u64)hi << 32) | lo;
+}
+
+__device__ __forceinline__ u64 shfl64(u64 v, int src) {
+  u32 lo = (u32)v, hi = (u32)(v >> 32);
+  lo = __shfl(lo, src);
+  hi = __shfl(hi, src);
+  return ((u64)hi << 32) | lo;
+}
+
+__device__ __forceinline__ u64 shfl_up64(u64 v, int d) {
+  u32 lo = (u32)v, hi = (u32)(v >> 32);
+  lo = __shfl_up(lo, d);
+  hi = __shfl_up(hi, d);
+  return ((u64)hi << 32) | lo;
+}
+
+// Inclusive scan of the affine chain over lanes 0..kN-1: on return lane l holds
+// sum_{k<=l} K2^(l-k) * d_k.
+template <int kN>
+__device__ __forceinline__ u64 chain_scan(u64 d, int lane) {
+#pragma unroll
+  for (int o = 1; o < kN; o <<= 1) {
+    const u64 up = shfl_up64(d, o);
+    if (lane >= o) d += ipow(K2, o) * up;
+  }
+  return d;
+}
+
+// ---- fast path: block sizes 16, 32, 64 -------------------------------------------------------
+template <int kB>
+__global__ __launch_bounds__(kHashWaves* kWave) void block_hash_pow2_kernel(
+    const int32_t* __restrict__ tokens, const int64_t* __restrict__ tok_off,
+    const int64_t* __restrict__ blk_off, u64 seed, u64* __restrict__ hash_out) {
+  static_assert(kB == 16 || kB == 32 || kB == 64, "block size");
+  constexpr int kNB = kTileTokens / kB;   // blocks per tile
+  constexpr int kGroups = kWave / kB;     // blocks covered by one 64-token load
+  constexpr int kLgB = kB == 16 ? 4 : (kB == 32 ? 5 : 6);
+  __shared__ u64 lds_aggr[2][kHashWaves];
+
+  const int r = blockIdx.x;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+  const int64_t t0 = tok_off[r];
+  const int64_t b0 = blk_off[r];
+  const int64_t n_r = blk_off[r + 1] - b0;
+  if (n_r <= 0) return;
+  const int64_t n_tok = n_r * kB;  // tokens that belong to full blocks
+  const int32_t* tok = tokens + t0;
+  u64* out = hash_out + b0;
+
+  const u64 pos_const = K0 * (u64)((lane & (kB - 1)) + 1);
+  // K2^(lane+1): weight of the carry-in at this lane's block
+  u64 carry_w = 1;
+  {
+    u64 sq = K2;
+    for (int bit = 0; bit < 7; ++bit) {
+      if ((lane + 1) >> bit & 1) carry_w *= sq;
+      sq *= sq;
+    }
+  }
+  // lane that holds block `lane`'s sum after the butterfly
+  const int src_lane = ((lane % kGroups) * kB + ((lane / kGroups) << (kLgB - 4))) & (kWave - 1);
+
+  u64 carry = fin(seed ^ K3);  // chain state before the first block of this iteration's tiles
+  const int64_t n_tiles = (n_r + kNB - 1) / kNB;
+  int parity = 0;
+  for (int64_t tile0 = 0; tile0 < n_tiles; tile0 += kHashWaves, parity ^= 1) {
+    const int64_t tile = tile0 + wave;
+    const int64_t tbase = tile * kTileTokens;
+    u64 p[kLoads];
+    // 16 coalesced loads; tokens past the last full block read as 0 and are never used
+    int32_t raw[kLoads];
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+      const int64_t idx = tbase + k * kWave + lane;
+      raw[k] = (tile < n_tiles && idx < n_tok) ? __builtin_nontemporal_load(tok + idx) : 0;
+    }
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+      const u64 y = ((u64)(u32)raw[k] ^ pos_const) * K1;
+      p[k] = y ^ (y >> 32);
+    }
+    // transposing butterfly: 16 partials per lane -> 1, summed over the lanes of a block
+    u64 q8[8], q4[4], q2[2], c;
+    {
+      const bool up = lane & (kB / 2);
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const u64 send = up ? p[t] : p[t + 8];
+        const u64 keep = up ? p[t + 8] : p[t];
+        q8[t] = keep + shfl_xor64(send, kB / 2);
+      }
+    }
+    {
+      const bool up = lane & (kB / 4);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const u64 send = up ? q8[t] : q8[t + 4];
+        const u64 keep = up ? q8[t + 4] : q8[t];
+        q4[t] = keep + shfl_xor64(send, kB / 4);
+      }
+    }
+    {
+      const bool up = lane & (kB / 8);
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const u64 send = up ? q4[t] : q4[t + 2];
+        const u64 keep = up ? q4[t + 2] : q4[t];
+        q2[t] = keep + shfl_xor64(send, kB / 8);
+      }
+    }
+    {
+      const bool up = lane & (kB / 16);
+      const u64 send = up ? q2[0] : q2[1];
+      const u64 keep = up ? q2[1] : q2[0];
+      c = keep + shfl_xor64(send, kB / 16);
+    }
+#pragma unroll
+    for (int m = kB / 32; m >= 1; m >>= 1) c += shfl_xor64(c, m);
+    // now the lane with load index k = (lane >> (kLgB-4)) & 15 and group g = lane / kB holds the
+    // sum of block k*kGroups + g; bring block `lane` to lane `lane`
+    c = shfl64(c, src_lane);
+    const int64_t jb = tile * kNB + lane;  // block index inside the request
+    const bool valid = lane < kNB && jb < n_r;
+    u64 d = valid ? fin(c) : 0ull;
+    const u64 local = chain_scan<kNB>(d, lane);
+    // tile aggregate = scan value at the tile's last block (earlier tiles are always full)
+    const u64 aggr = shfl64(local, kNB - 1);
+    if (lane == 0) lds_aggr[parity][wave] = aggr;
+    __syncthreads();
+    u64 cin = carry;
+    for (int w = 0; w < wave; ++w) cin = ipow(K2, kNB) * cin + lds_aggr[parity][w];
+    if (valid) out[jb] = out_hash(carry_w * cin + local);
+    // chain state after all tiles of this iteration (only used if another iteration follows,
+    // in which case every tile of this one was full)
+    for (int w = 0; w < kHashWaves; ++w) carry = ipow(K2, kNB) * carry + lds_aggr[parity][w];
+  }
+}
+
+// ---- general path: any block size in [1, 1024] ------------------------------------------------
+// Phase 1: each wavefront reduces whole blocks to digests and parks them in hash_out.
+// Phase 2: wavefront 0 runs the chain over the request's digests, 64 blocks at a time.
+__global__ __launch_bounds__(kHashWaves* kWave) void block_hash_general_kernel(
+    const int32_t* __restrict__ tokens, const int64_t* __restrict__ tok_off,
+    const int64_t* __restrict__ blk_off, int block_size, u64 seed, u64* __restrict__ hash_out) {
+  const int r = blockIdx.x;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+  const int64_t b0 = blk_off[r];
+  const int64_t n_r = blk_off[r + 1] - b0;
+  if (n_r <= 0) return;
+  const int32_t* tok = tokens + tok_off[r];
+  u64* out = hash_out + b0;
+  for (int64_t j = wave; j < n_r; j += kHashWaves) {
+    const int32_t* blk = tok + j * block_size;
+    u64 c = 0;
+    for (int i = lane; i < block_size; i += kWave) {
+      const u64 y = ((u64)(u32)blk[i] ^ (K0 * (u64)(i + 1))) * K1;
+      c += y ^ (y >> 32);
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) c += shfl_xor64(c, m);
+    if (lane == 0) out[j] = fin(c);
+  }
+  __syncthreads();  // digests written by this workgroup are visible to it after the barrier
+  if (wave != 0) return;
+  u64 carry_w = 1;
+  {
+    u64 sq = K2;
+    for (int bit = 0; bit < 7; ++bit) {
+      if ((lane + 1) >> bit & 1) carry_w *= sq;
+      sq *= sq;
+    }
+  }
+  u64 carry = fin(seed ^ K3);
+  for (int64_t base = 0; base < n_r; base += kWave) {
+    const int64_t j = base + lane;
+    const u64 d = j < n_r ? out[j] : 0ull;
+    const u64 local = chain_scan<kWave>(d, lane);
+    const u64 s = carry_w * carry + local;
+    if (j < n_r) out[j] = out_hash(s);
+    carry = shfl64(s, kWave - 1);
+  }
+}
+
+}  // namespace
+}  // namespace aibx
+
+extern "C" int aibx_block_hash(const int32_t* d_tokens, const int64_t* d_tok_off,
+                               const int64_t* d_blk_off, int32_t n_req, int64_t n_blocks_total,
+                               int32_t block_size, uint64_t seed, uint64_t* d_hash_out,
+                               void* stream) {
+  using namespace aibx;
+  if (n_req < 0 || n_blocks_total < 0 || block_size < 1 || block_size > 1024) return AIBX_ERR_INVALID_ARG;
+  if (n_req == 0 || n_blocks_total == 0) return AIBX_OK;
+  if (!d_tokens || !d_tok_off || !d_blk_off || !d_hash_out) return AIBX_ERR_INVALID_ARG;
+  if (!aligned(d_tokens, 4) || !aligned(d_tok_off, 8) || !aligned(d_blk_off, 8) || !aligned(d_hash_out, 8))
+    return AIBX_ERR_ALIGN;
+  hipStream_t st = as_stream(stream);
+  dim3 grid((u32)n_req), block(kHashWaves * kWave);
+  switch (block_size) {
+    case 16: block_hash_pow2_kernel<16><<<grid, block, 0, st>>>(d_tokens, d_tok_off, d_blk_off, seed, d_hash_out); break;
+    case 32: block_hash_pow2_kernel<32><<<grid, block, 0, st>>>(d_tokens, d_tok_off, d_blk_off, seed, d_hash_out); break;
+    case 64: block_hash_pow2_kernel<64><<<grid, block, 0, st>>>(d_tokens, d_tok_off, d_blk_off, seed, d_hash_out); break;
+    default:
+      block_hash_general_kernel<<<grid, block, 0, st>>>(d_tokens, d_tok_off, d_blk_off, block_size, seed, d_hash_out);
+  }
+  return launch_status();
+}

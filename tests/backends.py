@@ -60,3 +60,176 @@ class OracleBackend:
         ids = np.asarray(slot_ids, dtype=np.int64)
         st = self.staging.reshape(-1, self.stride)
         return st[ids, : self.geom.blk_bytes].copy()
+
+
+class HipIndex:
+    """Index handle over the HIP library, with the same surface as oracle.Index."""
+
+    def __init__(self, n_slots, stream=None):
+        import torch
+        import paper_2504_03648_amd as aibx
+        self.t, self.a = torch, aibx
+        self.n_slots = int(n_slots)
+        nbytes = aibx.aibx_index_storage_bytes(self.n_slots)
+        self.storage = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        self.h = aibx.aibx_index_create(self.storage, self.n_slots)
+        self.c_ins = torch.zeros(3, dtype=torch.int64, device="cuda")
+        self.c_ev = torch.zeros(2, dtype=torch.int64, device="cuda")
+
+    def __del__(self):
+        if getattr(self, "h", None) is not None:
+            self.a.aibx_index_destroy(self.h)
+            self.h = None
+
+    def _dev(self, x, dtype=np.uint64):
+        x = np.ascontiguousarray(x, dtype=dtype)
+        if dtype == np.uint64:
+            x = x.view(np.int64)
+        return self.t.from_numpy(x.copy()).cuda()
+
+    @staticmethod
+    def _host_u64(t):
+        return t.cpu().numpy().view(np.uint64)
+
+    @property
+    def counters_insert(self):
+        return self._host_u64(self.c_ins)
+
+    @property
+    def counters_evict(self):
+        return self._host_u64(self.c_ev)
+
+    def clear(self):
+        self.a.aibx_index_clear(self.h)
+
+    def insert(self, keys, values):
+        k, v = self._dev(keys), self._dev(values)
+        assert k.shape == v.shape
+        self.a.aibx_index_insert(self.h, k, v, k.numel(), self.c_ins)
+
+    def evict(self, keys):
+        k = self._dev(keys)
+        out = self.t.empty_like(k)
+        self.a.aibx_index_evict(self.h, k, k.numel(), out, self.c_ev)
+        return self._host_u64(out)
+
+    def count(self):
+        n = self.t.empty(1, dtype=self.t.int64, device="cuda")
+        self.a.aibx_index_count(self.h, n)
+        return int(n.item())
+
+    def dump(self):
+        cap = self.count()
+        k = self.t.empty(max(cap, 1), dtype=self.t.int64, device="cuda")
+        v = self.t.empty_like(k)
+        n = self.t.empty(1, dtype=self.t.int64, device="cuda")
+        self.a.aibx_index_dump(self.h, k, v, cap, n)
+        assert int(n.item()) == cap
+        hk, hv = self._host_u64(k)[:cap], self._host_u64(v)[:cap]
+        order = np.argsort(hk, kind="stable")
+        return hk[order], hv[order]
+
+    def match(self, hashes, blk_off):
+        h = self._dev(hashes)
+        bo = self._dev(blk_off, np.int64)
+        n_req = bo.numel() - 1
+        values = self.t.empty_like(h)
+        mlen = self.t.full((max(n_req, 0),), -7, dtype=self.t.int32, device="cuda")
+        self.a.aibx_prefix_match(self.h, h, bo, n_req, h.numel(), values, mlen)
+        return self._host_u64(values), mlen.cpu().numpy()
+
+
+class HipBackend:
+    """The HIP library through its Python binding; host arrays in, host arrays out."""
+    name = "hip"
+
+    def __init__(self, two_streams=True):
+        import torch
+        import paper_2504_03648_amd as aibx
+        self.t, self.a = torch, aibx
+        self.two_streams = two_streams
+        self.pool = self.staging = self.geom = self.desc = None
+
+    def _dev(self, x, dtype):
+        return self.t.from_numpy(np.ascontiguousarray(x, dtype=dtype).copy()).cuda()
+
+    def block_hash(self, tokens, tok_off, blk_off, block_size, seed):
+        t = self._dev(tokens, np.int32)
+        to, bo = self._dev(tok_off, np.int64), self._dev(blk_off, np.int64)
+        n_req = len(tok_off) - 1
+        n_blocks = int(blk_off[-1]) if n_req >= 0 else 0
+        out = self.t.full((n_blocks,), -1, dtype=self.t.int64, device="cuda")
+        self.a.aibx_block_hash(t, to, bo, n_req, n_blocks, block_size, seed, out)
+        return out.cpu().numpy().view(np.uint64)
+
+    def index_create(self, n_slots):
+        return HipIndex(n_slots)
+
+    def pool_create(self, geom, kv_dtype, cfg, host_bytes=None):
+        """Same bytes as the oracle backend's pool (generated on the host, uploaded)."""
+        from workloads import fill_pool_numpy
+        self.geom = geom
+        if host_bytes is None:
+            host_bytes = fill_pool_numpy(geom, kv_dtype, cfg)
+        self.pool = self.t.from_numpy(host_bytes).cuda()
+        self.desc = self.a.make_pool_desc(self.pool, *geom.as_tuple())
+
+    def staging_create(self, n_blocks, stride):
+        self.stride = int(stride)
+        self.staging = self.t.zeros(int(n_blocks) * self.stride, dtype=self.t.uint8, device="cuda")
+
+    def _ids(self, page_ids, slot_ids):
+        p = self._dev(page_ids, np.int32)
+        s = None if slot_ids is None else self._dev(slot_ids, np.int32)
+        n = p.numel()
+        if n:
+            smax = n - 1 if slot_ids is None else int(np.max(slot_ids))
+            smin = 0 if slot_ids is None else int(np.min(slot_ids))
+            assert smin >= 0 and (smax + 1) * self.stride <= self.staging.numel()
+        return p, s, n
+
+    def gather(self, page_ids, slot_ids, stream=None):
+        p, s, n = self._ids(page_ids, slot_ids)
+        bad = self.t.zeros(1, dtype=self.t.int64, device="cuda")
+        self.a.aibx_kv_gather(self.desc, p, s, n, self.staging, self.stride, bad, stream)
+        return int(bad.item())
+
+    def scatter(self, page_ids, slot_ids, stream=None):
+        p, s, n = self._ids(page_ids, slot_ids)
+        bad = self.t.zeros(1, dtype=self.t.int64, device="cuda")
+        self.a.aibx_kv_scatter(self.desc, p, s, n, self.staging, self.stride, bad, stream)
+        return int(bad.item())
+
+    def gather_scatter_pair(self, g_pages, g_slots, s_pages, s_slots):
+        """Gather and scatter enqueued on two streams so that they overlap on the GPU."""
+        t = self.t
+        if not self.two_streams:
+            return (self.gather(g_pages, g_slots), self.scatter(s_pages, s_slots))
+        gp, gs, gn = self._ids(g_pages, g_slots)
+        sp, ss, sn = self._ids(s_pages, s_slots)
+        bad = t.zeros(2, dtype=t.int64, device="cuda")
+        t.cuda.synchronize()
+        sa, sb = t.cuda.Stream(), t.cuda.Stream()
+        self.a.aibx_kv_gather(self.desc, gp, gs, gn, self.staging, self.stride, bad[0:1], sa)
+        self.a.aibx_kv_scatter(self.desc, sp, ss, sn, self.staging, self.stride, bad[1:2], sb)
+        sa.synchronize()
+        sb.synchronize()
+        b = bad.cpu().numpy()
+        return (int(b[0]), int(b[1]))
+
+    def _planes(self):
+        g = self.geom
+        return self.pool.view(g.n_seg, g.n_pages, g.seg_bytes)
+
+    def fill_pages(self, page_ids, byte):
+        ids = self._dev(page_ids, np.int64)
+        self._planes()[:, ids, :] = byte
+
+    def read_pages(self, page_ids):
+        ids = self._dev(page_ids, np.int64)
+        return self._planes()[:, ids, :].permute(1, 0, 2).contiguous().view(len(page_ids), -1).cpu().numpy()
+
+    def read_slots(self, slot_ids):
+        ids = self._dev(slot_ids, np.int64)
+        st = self.staging.view(-1, self.stride)
+        return st[ids, : self.geom.blk_bytes].cpu().numpy()

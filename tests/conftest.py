@@ -25,3 +25,11 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(autouse=True)
+def _announce_gpu_case(request):
+    """Names the GPU case on stdout before it runs, so that a run cut short still says where."""
+    if "gpu" in request.keywords:
+        print(f"\n[gpu-case] {request.node.nodeid}", flush=True)
+    yield

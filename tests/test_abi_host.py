@@ -1,0 +1,83 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2504_03648_amd import binding
+    return binding.load()
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "aibx.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(aibx_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    from paper_2504_03648_amd import binding
+    names = _declared()
+    assert len(names) >= 16
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_version_and_strerror(lib):
+    assert lib.aibx_version() >= 100 and lib.aibx_hash_version() == 1
+    assert lib.aibx_strerror(0) == b"ok"
+    for code in (-1, -2, -3, -4, -99):
+        assert len(lib.aibx_strerror(code)) > 0
+
+
+def test_storage_bytes_rules(lib):
+    out = C.c_size_t()
+    assert lib.aibx_index_storage_bytes(1 << 20, C.byref(out)) == 0 and out.value == 16 << 20
+    assert lib.aibx_index_storage_bytes(8, C.byref(out)) == 0 and out.value == 128
+    for bad in (0, 4, 12, 1000, (1 << 20) + 8, 1 << 40):
+        assert lib.aibx_index_storage_bytes(bad, C.byref(out)) == -3
+    assert lib.aibx_index_storage_bytes(64, None) == -1
+
+
+def test_argument_errors_are_raised_before_any_launch(lib):
+    from paper_2504_03648_amd.binding import PoolDesc
+    fake = C.c_void_p(0x1000)         # never dereferenced: every call below must fail on the host
+    odd = C.c_void_p(0x1004)
+    # block hash
+    assert lib.aibx_block_hash(fake, fake, fake, -1, 0, 16, 0, fake, None) == -1
+    assert lib.aibx_block_hash(fake, fake, fake, 1, 1, 0, 0, fake, None) == -1
+    assert lib.aibx_block_hash(fake, fake, fake, 1, 1, 1025, 0, fake, None) == -1
+    assert lib.aibx_block_hash(None, fake, fake, 1, 1, 16, 0, fake, None) == -1
+    assert lib.aibx_block_hash(fake, odd, fake, 1, 1, 16, 0, fake, None) == -2
+    assert lib.aibx_block_hash(fake, fake, fake, 0, 0, 16, 0, fake, None) == 0      # empty batch
+    # index
+    h = C.c_void_p()
+    assert lib.aibx_index_create(None, 1 << 20, 64, None, C.byref(h)) == -1
+    assert lib.aibx_index_create(fake, 1 << 20, 100, None, C.byref(h)) == -3
+    assert lib.aibx_index_create(fake, 16, 64, None, C.byref(h)) == -1               # storage too small
+    assert lib.aibx_index_create(odd, 1 << 20, 64, None, C.byref(h)) == -2
+    assert lib.aibx_index_insert(None, fake, fake, 1, None, None) == -1
+    assert lib.aibx_index_evict(None, fake, 1, None, None, None) == -1
+    assert lib.aibx_prefix_match(None, fake, fake, 1, 1, None, fake, None) == -1
+    assert lib.aibx_index_destroy(None) == 0
+    # copies
+    d = PoolDesc(0x1000, 2, 1 << 20, 4096, 4096, 16)
+    assert lib.aibx_kv_gather(C.byref(d), fake, None, -1, fake, 8192, None, None) == -1
+    assert lib.aibx_kv_gather(C.byref(d), fake, None, 0, fake, 8192, None, None) == 0
+    assert lib.aibx_kv_gather(None, fake, None, 1, fake, 8192, None, None) == -1
+    assert lib.aibx_kv_gather(C.byref(d), fake, None, 1, fake, 4096, None, None) == -1  # stride < block
+    assert lib.aibx_kv_gather(C.byref(d), fake, None, 1, fake, 8200, None, None) == -2
+    assert lib.aibx_kv_scatter(C.byref(d), fake, None, 1, odd, 8192, None, None) == -2
+    bad = PoolDesc(0x1000, 2, 1 << 20, 4096, 4100, 16)
+    assert lib.aibx_kv_gather(C.byref(bad), fake, None, 1, fake, 8208, None, None) == -1  # page_stride < seg
+    bad = PoolDesc(0x1000, 2, 1 << 20, 4112, 4104, 16)
+    assert lib.aibx_kv_gather(C.byref(bad), fake, None, 1, fake, 8208, None, None) == -2
+    bad = PoolDesc(0x1000, 0, 1 << 20, 4096, 4096, 16)
+    assert lib.aibx_kv_scatter(C.byref(bad), fake, None, 1, fake, 8192, None, None) == -1

@@ -1,0 +1,274 @@
+"""Parity of the HIP library (through its C ABI) with the CPU oracle, bit for bit, on small
+inputs that still span several tiles and ragged tails, plus the edge cases."""
+import numpy as np
+import pytest
+
+import oracle
+from backends import HipBackend, HipIndex, OracleBackend
+from workloads import Geometry, make_tokens, make_workload, flows
+
+pytestmark = pytest.mark.gpu
+NO = np.uint64(0xFFFFFFFFFFFFFFFF)
+
+
+@pytest.fixture(scope="module")
+def hip():
+    return HipBackend()
+
+
+# ---- block hash --------------------------------------------------------------------------------
+def _ragged(rng, n_req, lo, hi, neg=False):
+    lens = rng.integers(lo, hi + 1, size=n_req)
+    tok_off = np.zeros(n_req + 1, dtype=np.int64)
+    np.cumsum(lens, out=tok_off[1:])
+    if neg:
+        tok = rng.integers(-2**31, 2**31, size=int(tok_off[-1]), dtype=np.int64).astype(np.int32)
+    else:
+        tok = rng.integers(0, 32000, size=int(tok_off[-1]), dtype=np.int32)
+    return tok, tok_off, lens
+
+
+@pytest.mark.parametrize("B", [16, 32, 64, 1, 5, 17, 100, 128, 1024])
+def test_block_hash_ragged(hip, B):
+    rng = np.random.default_rng(B)
+    # lengths from below one block to many tiles (a tile is 1024 tokens), with ragged tails
+    tok, tok_off, lens = _ragged(rng, 37, 0, max(40 * B, 5000), neg=True)
+    lens[3] = 0
+    lens[5] = B - 1 if B > 1 else 0
+    lens[7] = B
+    lens[9] = 4096 * 3 + B // 2
+    np.cumsum(lens, out=tok_off[1:])
+    tok = rng.integers(-2**31, 2**31, size=int(tok_off[-1]), dtype=np.int64).astype(np.int32)
+    blk_off = np.zeros(len(lens) + 1, dtype=np.int64)
+    np.cumsum(lens // B, out=blk_off[1:])
+    for seed in (0, 0xDEADBEEF12345678):
+        want = oracle.block_hash(tok, tok_off, blk_off, B, seed)
+        got = hip.block_hash(tok, tok_off, blk_off, B, seed)
+        assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_block_hash_configs_full_size(hip, cfg):
+    wl = make_workload(cfg, "full")
+    want = oracle.block_hash(wl.tokens, wl.tok_off, wl.blk_off, wl.block_size, 0)
+    got = hip.block_hash(wl.tokens, wl.tok_off, wl.blk_off, wl.block_size, 0)
+    assert np.array_equal(got, want)
+
+
+def test_block_hash_golden_vector_and_empty(hip):
+    t = np.arange(32, dtype=np.int32)
+    got = hip.block_hash(t, [0, 32], [0, 2], 16, 0)
+    assert [int(x) for x in got] == [0xF95A27A48F22F512, 0x7FDA0CD7157322A0]
+    assert len(hip.block_hash(t[:0], [0], [0], 16, 0)) == 0
+    assert len(hip.block_hash(t[:7], [0, 7], [0, 0], 16, 0)) == 0
+
+
+# ---- index -------------------------------------------------------------------------------------
+def _same_bucket_keys(rng, n_slots, n):
+    """Keys whose home bucket (multiplicative hash, top bits) collide often: draw many, keep
+    those falling into two buckets."""
+    nb = max(n_slots // 8, 1)
+    lg = int(np.log2(nb))
+    keys = rng.integers(1, 2**63, size=200 * n, dtype=np.uint64)
+    if lg == 0:
+        return keys[:n]
+    home = (keys * np.uint64(0x9E3779B97F4A7C15)) >> np.uint64(64 - lg)
+    pick = keys[(home == home[0]) | (home == (home[0] + np.uint64(1)) % np.uint64(nb))]
+    return np.concatenate([pick[: n // 2], keys[: n - min(len(pick), n // 2)]])
+
+
+@pytest.mark.parametrize("n_slots", [8, 16, 64, 1024])
+def test_index_random_ops_against_oracle(n_slots):
+    rng = np.random.default_rng(n_slots)
+    gi, oi = HipIndex(n_slots), oracle.Index(n_slots)
+    universe = np.unique(_same_bucket_keys(rng, n_slots, 3 * n_slots))
+    for step in range(120):
+        op = rng.integers(0, 4)
+        m = int(rng.integers(0, min(len(universe), n_slots // 2 + 3)))
+        k = rng.choice(universe, size=m, replace=False)
+        if op <= 1:
+            if gi.count() + m > n_slots:      # which keys survive an overflow is unspecified
+                continue
+            v = rng.integers(0, 2**40, size=m, dtype=np.uint64)
+            gi.insert(k, v)
+            oi.insert(k, v)
+        elif op == 2:
+            assert np.array_equal(gi.evict(k), oi.evict(k))
+        else:
+            gv, gm = gi.match(k, [0, m])
+            ov, om = oi.match(k, [0, m])
+            assert np.array_equal(gv, ov) and np.array_equal(gm, om)
+        assert gi.count() == oi.count()
+    gk, gv = gi.dump()
+    ok, ov = oi.dump()
+    assert np.array_equal(gk, ok) and np.array_equal(gv, ov)
+    assert np.array_equal(gi.counters_insert, oi.counters_insert)
+    assert np.array_equal(gi.counters_evict, oi.counters_evict)
+
+
+def test_index_overflow_counts():
+    """m > n_slots distinct keys into an empty table: exactly n_slots succeed, the rest are
+    counted full; every survivor is found with its value."""
+    for n_slots in (8, 64, 512):
+        rng = np.random.default_rng(n_slots + 1)
+        gi = HipIndex(n_slots)
+        keys = np.unique(rng.integers(1, 2**63, size=2 * n_slots + 7, dtype=np.uint64))
+        gi.insert(keys, keys >> np.uint64(3))
+        assert list(gi.counters_insert) == [n_slots, 0, len(keys) - n_slots]
+        assert gi.count() == n_slots
+        v, _ = gi.match(keys, [0, len(keys)])
+        found = v != NO
+        assert found.sum() == n_slots and np.array_equal(v[found], keys[found] >> np.uint64(3))
+        # a full table still updates present keys and still reports absent ones as missing
+        gi.insert(keys[found][:5], np.arange(5, dtype=np.uint64))
+        assert list(gi.counters_insert) == [n_slots, 5, len(keys) - n_slots]
+        ev = gi.evict(keys)
+        assert (ev != NO).sum() == n_slots and gi.count() == 0
+        # tombstones everywhere: inserts must still succeed by reusing them
+        gi.insert(keys[: n_slots // 2], keys[: n_slots // 2])
+        assert gi.count() == n_slots // 2
+        v, _ = gi.match(keys[: n_slots // 2], [0, n_slots // 2])
+        assert np.array_equal(v, keys[: n_slots // 2])
+
+
+def test_index_duplicates_and_reserved_keys():
+    gi, oi = HipIndex(256), oracle.Index(256)
+    k = np.array([5, 5, 7, 5, 9, 7, 5, 5, 5, 5, 11], dtype=np.uint64)
+    v = k * np.uint64(100)
+    for ix in (gi, oi):
+        ix.insert(k, v)
+        ix.insert(np.array([0, NO, 13], dtype=np.uint64), np.array([1, 2, 3], dtype=np.uint64))
+    assert np.array_equal(gi.counters_insert, oi.counters_insert)
+    assert list(gi.counters_insert) == [5, 7, 2]
+    assert all(np.array_equal(a, b) for a, b in zip(gi.dump(), oi.dump()))
+    q = np.array([0, NO, 5, 6], dtype=np.uint64)
+    assert np.array_equal(gi.match(q, [0, 4])[0], oi.match(q, [0, 4])[0])
+    assert np.array_equal(gi.evict(q), oi.evict(q))
+    # duplicate keys in one evict batch: exactly one occurrence gets the value
+    ev = gi.evict(np.array([7, 7, 7, 9], dtype=np.uint64))
+    assert sorted(int(x) for x in ev[:3]) == [700, int(NO), int(NO)] and ev[3] == 900
+    assert list(gi.counters_evict) == [3, 5]
+    # duplicates with different values: any one of them may win
+    gi.insert(np.array([21, 21, 21], dtype=np.uint64), np.array([1, 2, 3], dtype=np.uint64))
+    assert int(gi.match(np.array([21], dtype=np.uint64), [0, 1])[0][0]) in (1, 2, 3)
+
+
+def test_index_large_batch_with_shared_prefix_duplicates():
+    """A batch shaped like the real preload: every block of every request, shared prefixes
+    repeated, 100k+ keys in one call, then evict half and match."""
+    tok, tok_off, blk_off = make_tokens(3, 0, 64)
+    h = oracle.block_hash(tok, tok_off, blk_off, 16, 0)
+    uniq, inv = np.unique(h, return_inverse=True)
+    vals = (np.arange(len(uniq), dtype=np.uint64) + np.uint64(7))[inv]
+    gi, oi = HipIndex(1 << 16), oracle.Index(1 << 16)
+    for ix in (gi, oi):
+        ix.insert(h, vals)
+    assert np.array_equal(gi.counters_insert, oi.counters_insert)
+    ev = uniq[::2]
+    assert np.array_equal(gi.evict(ev), oi.evict(ev))
+    gv, gm = gi.match(h, blk_off)
+    ov, om = oi.match(h, blk_off)
+    assert np.array_equal(gv, ov) and np.array_equal(gm, om)
+    assert gi.count() == oi.count()
+    assert all(np.array_equal(a, b) for a, b in zip(gi.dump(), oi.dump()))
+    gi.clear()
+    assert gi.count() == 0
+
+
+def test_match_edge_cases():
+    gi, oi = HipIndex(64), oracle.Index(64)
+    keys = np.arange(1, 30, dtype=np.uint64)
+    for ix in (gi, oi):
+        ix.insert(keys[::2], keys[::2])
+    # requests with 0 blocks, 1 block, exactly 64, 65 and 300 blocks (several tiles per request)
+    sizes = [0, 1, 64, 65, 300, 0, 3]
+    blk_off = np.zeros(len(sizes) + 1, dtype=np.int64)
+    np.cumsum(sizes, out=blk_off[1:])
+    rng = np.random.default_rng(0)
+    h = rng.choice(keys, size=int(blk_off[-1])).astype(np.uint64)
+    h[blk_off[4]:blk_off[4] + 130] = 1          # a long matched run across tiles
+    gv, gm = gi.match(h, blk_off)
+    ov, om = oi.match(h, blk_off)
+    assert np.array_equal(gv, ov) and np.array_equal(gm, om)
+    assert gm[4] >= 130
+
+
+# ---- gather / scatter --------------------------------------------------------------------------
+@pytest.mark.parametrize("n_seg,seg_bytes,n_pages,n", [
+    (1, 262144, 40, 23), (64, 32768, 24, 17), (61, 73728, 12, 9), (5, 16, 50, 33),
+    (3, 4096 + 16, 30, 30), (2, 8192, 30, 1), (7, 48, 9, 64), (1, 16, 1, 1), (4, 12288, 20, 11)])
+def test_gather_scatter_parity(n_seg, seg_bytes, n_pages, n):
+    g = Geometry(n_seg, seg_bytes, n_pages)
+    rng = np.random.default_rng(n_seg * 1000 + n)
+    host = rng.integers(0, 256, size=g.pool_bytes, dtype=np.uint8)
+    ob, hb = OracleBackend(), HipBackend()
+    ob.geom, ob.pool = g, host.copy()
+    hb.pool_create(g, None, None, host_bytes=host.copy())
+    stride = g.blk_bytes + (32 if n_seg == 5 else 0)
+    n_slots = n + 3
+    for be in (ob, hb):
+        be.staging_create(n_slots, stride)
+    ids = rng.integers(0, n_pages, size=n).astype(np.int32)
+    if n > 4:
+        ids[1] = -1
+        ids[2] = n_pages           # bad page
+        ids[3] = 2**31 - 1         # bad page
+    slots = rng.permutation(n_slots)[:n].astype(np.int32)
+    all_slots = np.arange(n_slots, dtype=np.int32)
+    for sl in (None, slots):
+        bo, bh = ob.gather(ids, sl), hb.gather(ids, sl)
+        assert bo == bh == (2 if n > 4 else 0)
+        assert np.array_equal(hb.staging.cpu().numpy(), ob.staging)      # whole staging, padding included
+    # scatter distinct pages back from shuffled slots
+    pages = rng.permutation(n_pages)[: min(n, n_pages)].astype(np.int32)
+    sl = slots[: len(pages)]
+    assert ob.scatter(pages, sl) == hb.scatter(pages, sl) == 0
+    assert np.array_equal(hb.pool.cpu().numpy(), ob.pool)                # whole pool
+    assert np.array_equal(hb.read_slots(all_slots), ob.read_slots(all_slots))
+
+
+def test_gather_then_scatter_is_identity_on_the_pool():
+    g = Geometry(8, 32768, 300)
+    hb = HipBackend()
+    hb.pool_create(g, "bf16", 2)
+    keep = hb.pool.clone()
+    ids = np.random.default_rng(0).permutation(300)[:200].astype(np.int32)
+    hb.staging_create(200, g.blk_bytes)
+    assert hb.gather(ids, None) == 0
+    hb.fill_pages(ids, 0xA5)
+    assert not hb.t.equal(hb.pool, keep)
+    assert hb.scatter(ids, None) == 0
+    assert hb.t.equal(hb.pool, keep)
+
+
+# ---- whole flows on the small configs ----------------------------------------------------------
+@pytest.mark.parametrize("cfg", [1, 3, 4])
+def test_flow_match_roundtrip_small(cfg):
+    wl = make_workload(cfg, "small")
+    a = flows.flow_match_roundtrip(wl, OracleBackend())
+    hb = HipBackend()
+    b = flows.flow_match_roundtrip(wl, hb)
+    assert flows.traces_equal(a, b) == []
+    from workloads import fill_pool_numpy
+    assert np.array_equal(hb.pool.cpu().numpy(), fill_pool_numpy(wl.geom, wl.kv_dtype, wl.cfg))
+
+
+@pytest.mark.parametrize("layout", [None, "page-major"])
+def test_flow_offload_onload_small(layout):
+    wl = make_workload(2, "small", layout=layout)
+    ob, hb = OracleBackend(), HipBackend()
+    a = flows.flow_offload_onload(wl, ob)
+    b = flows.flow_offload_onload(wl, hb)
+    assert flows.traces_equal(a, b) == []
+    assert np.array_equal(hb.pool.cpu().numpy(), ob.pool)
+    assert np.array_equal(hb.staging.cpu().numpy(), ob.staging)
+
+
+def test_flow_stress_small_two_streams():
+    wl = make_workload(5, "small")
+    ob, hb = OracleBackend(), HipBackend(two_streams=True)
+    a = flows.flow_stress(wl, ob, n_rounds=6, q=512)
+    b = flows.flow_stress(wl, hb, n_rounds=6, q=512)
+    assert flows.traces_equal(a, b) == []
+    assert np.array_equal(hb.pool.cpu().numpy(), ob.pool)
+    assert np.array_equal(hb.staging.cpu().numpy(), ob.staging)
