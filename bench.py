@@ -1,0 +1,296 @@
+#!/usr/bin/env python3
+"""Benchmark of the KV-cache hot path on one MI355X.
+
+A step is one pass of the whole path over the Llama-3-8B-shaped workload (64 requests x 4096
+tokens, 16-token blocks, 20,000-page pool of 2 MiB blocks in 64 planes, 2^20-slot index at load
+0.5): clear + preload the index, hash every request, index every block, gather the cold half of
+the resident blocks to staging (offload), re-point and evict index entries, match every request,
+scatter the matched staged blocks back into the pool (onload), update the index. Every array the
+step reads is resident in HBM before the clock starts.
+
+Prints ONE JSON line. `value` = bytes read + written by the gathers and scatters of a step divided
+by the whole step's time. `roofline` is the gather kernel against 8 TB/s. `hash_match` is the
+scaled batch (the same request mix replicated until >= 4 Mi blocks) against its 152 B/block HBM
+roofline. `cpu_baseline` is the CPU oracle on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+STAGED = np.uint64(1) << np.uint64(62)
+NO_VALUE = np.uint64(0xFFFFFFFFFFFFFFFF)
+
+# HBM bytes per gather launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the same
+# counters on a plain copy of known size; valid only for the kernel source it was taken on.
+MEASURED_TRAFFIC = {"kvcopy_sha1": None, "bytes_per_launch": None}
+
+
+def _u64(t):
+    return t.cpu().numpy().view(np.uint64)
+
+
+def _dev_u64(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint64).view(np.int64).copy()).cuda()
+
+
+def _kvcopy_sha1():
+    p = os.path.join(ROOT, "paper_2504_03648_amd", "csrc", "kvcopy.hip")
+    return hashlib.sha1(open(p, "rb").read()).hexdigest()
+
+
+class Step:
+    """Device-resident state and the call sequence of one step."""
+
+    def __init__(self, torch, aibx, wl):
+        from workloads import fill_pool_torch, filler_keys
+        from workloads.configs import ops_rng
+        self.t, self.a, self.wl = torch, aibx, wl
+        g = wl.geom
+        dev = "cuda"
+        self.tokens = torch.from_numpy(wl.tokens).to(dev)
+        self.tok_off = torch.from_numpy(wl.tok_off).to(dev)
+        self.blk_off = torch.from_numpy(wl.blk_off).to(dev)
+        self.N, self.R = wl.n_blocks, wl.n_req
+        self.hash = torch.empty(self.N, dtype=torch.int64, device=dev)
+        self.values = torch.empty(self.N, dtype=torch.int64, device=dev)
+        self.mlen = torch.empty(self.R, dtype=torch.int32, device=dev)
+        self.ev_out = None
+        self.ev_g0 = self.ev_g1 = None
+        self.pool = torch.empty(g.pool_bytes, dtype=torch.uint8, device=dev)
+        fill_pool_torch(self.pool, wl.kv_dtype, wl.cfg)
+        self.desc = aibx.make_pool_desc(self.pool, *g.as_tuple())
+        self.storage = torch.empty(aibx.aibx_index_storage_bytes(wl.n_slots), dtype=torch.uint8, device=dev)
+        self.ix = aibx.aibx_index_create(self.storage, wl.n_slots)
+        self.counters = torch.zeros(8, dtype=torch.int64, device=dev)
+        # ---- untimed planning pass: which keys / pages / slots each call names ----------------
+        aibx.aibx_block_hash(self.tokens, self.tok_off, self.blk_off, self.R, self.N, wl.block_size,
+                             wl.hash_seed, self.hash)
+        h = _u64(self.hash)
+        uniq, first, inv, cnt = np.unique(h, return_index=True, return_inverse=True, return_counts=True)
+        order = np.argsort(first, kind="stable")
+        rank_of_uniq = np.empty(len(uniq), dtype=np.int64)
+        rank_of_uniq[order] = np.arange(len(uniq))
+        dkeys, refcnt, rank = uniq[order], cnt[order], rank_of_uniq[inv]
+        assert len(dkeys) <= g.n_pages
+        dvalues = wl.page_perm[: len(dkeys)].astype(np.uint64)
+        self.block_values = _dev_u64(torch, dvalues[rank])
+        n_fill = max(0, wl.n_live_target - len(dkeys))
+        fk, fv = filler_keys(wl.cfg, n_fill)
+        self.fk, self.fv = _dev_u64(torch, fk), _dev_u64(torch, fv)
+        cold = np.lexsort((dkeys, refcnt))[: len(dkeys) // 2]
+        cold_keys, cold_pages = dkeys[cold], dvalues[cold].astype(np.int32)
+        n_cold = len(cold)
+        self.n_cold = n_cold
+        self.staging = torch.empty(n_cold * g.blk_bytes, dtype=torch.uint8, device=dev)
+        self.cold_keys = _dev_u64(torch, cold_keys)
+        self.cold_pages = torch.from_numpy(cold_pages.copy()).to(dev)
+        self.cold_slots = torch.arange(n_cold, dtype=torch.int32, device=dev)
+        self.cold_vals = _dev_u64(torch, STAGED | np.arange(n_cold, dtype=np.uint64))
+        rng = ops_rng(wl.cfg, 2)
+        dropped = cold_keys[rng.permutation(n_cold)[: n_cold // 10]]
+        self.dropped = _dev_u64(torch, dropped)
+        self.ev_out = torch.empty(len(dropped), dtype=torch.int64, device=dev)
+        # run the index part once to learn which staged blocks are on a matched prefix
+        self.n_on = 0
+        self._index_front()
+        aibx.aibx_prefix_match(self.ix, self.hash, self.blk_off, self.R, self.N, self.values, self.mlen)
+        values, mlen = _u64(self.values), self.mlen.cpu().numpy()
+        on_prefix = np.zeros(self.N, dtype=bool)
+        for r in range(self.R):
+            on_prefix[wl.blk_off[r]:wl.blk_off[r] + mlen[r]] = True
+        want = on_prefix & (values != NO_VALUE) & ((values & STAGED) != 0) & ((values >> np.uint64(63)) == 0)
+        on_keys, firsti = np.unique(h[want], return_index=True)
+        on_slots = (values[want][firsti] & ~STAGED).astype(np.int32)
+        new_pages = cold_pages[rng.permutation(n_cold)[: len(on_keys)]]
+        self.n_on = len(on_keys)
+        self.on_keys = _dev_u64(torch, on_keys)
+        self.on_slots = torch.from_numpy(on_slots.copy()).to(dev)
+        self.on_pages = torch.from_numpy(new_pages.copy()).to(dev)
+        self.on_vals = _dev_u64(torch, new_pages.astype(np.uint64))
+        self.plan_mlen = mlen.copy()
+        self.copy_bytes = 2 * (self.n_cold + self.n_on) * g.blk_bytes
+        self.gather_bytes = 2 * self.n_cold * g.blk_bytes
+        self.ev_g0 = self.ev_g1 = None
+        torch.cuda.synchronize()
+
+    def _index_front(self):
+        a, wl = self.a, self.wl
+        c = self.counters
+        a.aibx_index_clear(self.ix)
+        a.aibx_index_insert(self.ix, self.fk, self.fv, self.fk.numel(), c[0:3])
+        a.aibx_block_hash(self.tokens, self.tok_off, self.blk_off, self.R, self.N, wl.block_size,
+                          wl.hash_seed, self.hash)
+        a.aibx_index_insert(self.ix, self.hash, self.block_values, self.N, c[0:3])
+        if self.ev_g0 is not None:
+            self.ev_g0.record()
+        a.aibx_kv_gather(self.desc, self.cold_pages, self.cold_slots, self.n_cold, self.staging,
+                         wl.geom.blk_bytes, c[5:6])
+        if self.ev_g1 is not None:
+            self.ev_g1.record()
+        a.aibx_index_insert(self.ix, self.cold_keys, self.cold_vals, self.n_cold, c[0:3])
+        a.aibx_index_evict(self.ix, self.dropped, self.dropped.numel(), self.ev_out, c[3:5])
+
+    def run(self, events=None):
+        a, wl = self.a, self.wl
+        self.ev_g0, self.ev_g1 = events if events else (None, None)
+        self._index_front()
+        a.aibx_prefix_match(self.ix, self.hash, self.blk_off, self.R, self.N, self.values, self.mlen)
+        a.aibx_kv_scatter(self.desc, self.on_pages, self.on_slots, self.n_on, self.staging,
+                          wl.geom.blk_bytes, self.counters[5:6])
+        a.aibx_index_insert(self.ix, self.on_keys, self.on_vals, self.n_on, self.counters[0:3])
+
+
+def time_calls(torch, fn, reps, warm=2):
+    for _ in range(warm):
+        fn()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a, b in evs:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    ms = sorted(a.elapsed_time(b) for a, b in evs)
+    return ms[len(ms) // 2], ms[0]
+
+
+def scaled_hash_match(torch, aibx, cfg, step, min_blocks):
+    """Scaled batch: hash and match >= min_blocks blocks in one launch each, index unchanged."""
+    from workloads import make_scaled_tokens
+    tok, tok_off, blk_off = make_scaled_tokens(cfg, min_blocks)
+    N, R = int(blk_off[-1]), len(blk_off) - 1
+    d_tok = torch.from_numpy(tok).cuda()
+    d_to, d_bo = torch.from_numpy(tok_off).cuda(), torch.from_numpy(blk_off).cuda()
+    h = torch.empty(N, dtype=torch.int64, device="cuda")
+    v = torch.empty(N, dtype=torch.int64, device="cuda")
+    m = torch.empty(R, dtype=torch.int32, device="cuda")
+    B = step.wl.block_size
+    hash_ms, _ = time_calls(torch, lambda: aibx.aibx_block_hash(d_tok, d_to, d_bo, R, N, B, 0, h), 10)
+    match_ms, _ = time_calls(torch, lambda: aibx.aibx_prefix_match(step.ix, h, d_bo, R, N, v, m), 10)
+    per_block = 4 * B + 8 + 8 + 64 + 8
+    t = (hash_ms + match_ms) * 1e-3
+    rate = N / t
+    return {
+        "workload": f"config {cfg} request mix replicated to {R} requests / {N} blocks / {len(tok)} tokens",
+        "blocks_per_s": rate, "hash_ms": hash_ms, "match_ms": match_ms,
+        "hash_GBps": N * (4 * B + 8) / (hash_ms * 1e-3) / 1e9,
+        "match_Gprobes_per_s": N / (match_ms * 1e-3) / 1e9,
+        "roofline": {"bound": "hbm", "achieved": rate * per_block / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": rate * per_block / 1e9 / HBM_PEAK_GBPS, "bytes_per_block": per_block},
+    }
+
+
+def cpu_baseline(wl, gpu_hash, gpu_mlen_fn):
+    """The oracle on a bounded sample: hash+match of the whole native config, and gather+scatter
+    of 512 blocks on a 1024-page host mirror of the pool. Also cross-checks the GPU's hashes."""
+    import oracle
+    from workloads import Geometry
+    t0 = time.perf_counter()
+    h = oracle.block_hash(wl.tokens, wl.tok_off, wl.blk_off, wl.block_size, wl.hash_seed)
+    t_hash = time.perf_counter() - t0
+    checked = bool(np.array_equal(h, gpu_hash))
+    ix = oracle.Index(wl.n_slots)
+    ix.insert(h, np.arange(len(h), dtype=np.uint64))
+    t0 = time.perf_counter()
+    reps_m = 20
+    for _ in range(reps_m):
+        ix.match(h, wl.blk_off)
+    t_match = (time.perf_counter() - t0) / reps_m
+    g = Geometry(wl.geom.n_seg, wl.geom.seg_bytes, 1024)
+    tile = np.random.default_rng(0).integers(0, 256, size=1 << 26, dtype=np.uint8)
+    pool = np.tile(tile, g.pool_bytes // len(tile))
+    n = 512
+    staging = np.zeros(n * g.blk_bytes, dtype=np.uint8)
+    ids = np.random.default_rng(1).permutation(g.n_pages)[:n].astype(np.int32)
+    oracle.kv_gather(pool, g.as_tuple(), ids, None, staging, g.blk_bytes)        # touch pages once
+    reps = 6
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        oracle.kv_gather(pool, g.as_tuple(), ids, None, staging, g.blk_bytes)
+        oracle.kv_scatter(pool, g.as_tuple(), ids, None, staging, g.blk_bytes)
+    t_copy = (time.perf_counter() - t0) / (2 * reps)
+    return {
+        "value": 2 * n * g.blk_bytes / t_copy / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "sample": f"gather+scatter of {n} blocks of {g.blk_bytes} B on a {g.n_pages}-page host mirror, "
+                  f"{reps} repetitions; hash+match of the native config ({wl.n_blocks} blocks)",
+        "hash_match_blocks_per_s": wl.n_blocks / (t_hash + t_match),
+        "gpu_hashes_equal_oracle": checked,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="workload (2 = the one the metric is quoted on)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-scaled", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this path runs on ONE GPU (no sharding, no collectives); use --gpus 1")
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    import paper_2504_03648_amd as aibx
+    from workloads import make_workload
+    torch.cuda.set_device(0)
+    wl = make_workload(args.config, "full")
+    step = Step(torch, aibx, wl)
+    for _ in range(args.warmup):
+        step.run()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step.run(evs[k])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+    gather_ms = sum(a.elapsed_time(b) for a, b in evs) / args.steps
+    assert np.array_equal(step.mlen.cpu().numpy(), step.plan_mlen)
+    g = wl.geom
+    value = step.copy_bytes / (ms_per_step * 1e-3) / 1e9
+    achieved = step.gather_bytes / (gather_ms * 1e-3) / 1e9
+    # what a library device-to-device copy of the same volume reaches on this GPU, for context
+    src, dst = step.staging, step.pool[: step.staging.numel()]
+    plain_ms, _ = time_calls(torch, lambda: dst.copy_(src), 5)
+    plain_gbps = 2 * src.numel() / (plain_ms * 1e-3) / 1e9
+    traffic = None
+    if MEASURED_TRAFFIC["kvcopy_sha1"] == _kvcopy_sha1():
+        traffic = MEASURED_TRAFFIC["bytes_per_launch"]
+    out = {
+        "metric": "kv_gather_scatter_hbm_GBps", "value": value, "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8",
+        "data": "synthetic",
+        "config": {"workload": f"configs[{args.config - 1}] {wl.name}", "requests": wl.n_req,
+                   "tokens": int(wl.tok_off[-1]), "blocks": wl.n_blocks, "block_size": wl.block_size,
+                   "blk_bytes": g.blk_bytes, "n_seg": g.n_seg, "pool_pages": g.n_pages,
+                   "index_slots": wl.n_slots, "gathered_blocks": step.n_cold, "scattered_blocks": step.n_on},
+        "pct_of_peak": 100.0 * value / HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "kernel": "kv_copy_kernel<gather>",
+                     "bytes_per_launch": step.gather_bytes, "avg_launch_ms": gather_ms,
+                     "plain_d2d_copy_GBps": plain_gbps},
+    }
+    if not args.no_scaled:
+        out["hash_match"] = scaled_hash_match(torch, aibx, args.config, step, 4 << 20)
+        out["hash_match_blocks_per_s"] = out["hash_match"]["blocks_per_s"]
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, _u64(step.hash), None)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
