@@ -236,6 +236,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload (2 = the one the metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-scaled", action="store_true")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run a plain elementwise kernel that reads and writes the staging "
+                         "buffer once (known HBM bytes), for scaling profiler counters")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this path runs on ONE GPU (no sharding, no collectives); use --gpus 1")
@@ -284,6 +287,12 @@ def main():
                      "bytes_per_launch": step.gather_bytes, "avg_launch_ms": gather_ms,
                      "plain_d2d_copy_GBps": plain_gbps},
     }
+    if args.calibrate:
+        cal = step.staging.view(torch.int64)
+        cal.add_(1)
+        torch.cuda.synchronize()
+        out["calibration"] = {"kernel": "torch elementwise add_ (int64)", "bytes_read": cal.numel() * 8,
+                              "bytes_written": cal.numel() * 8}
     if not args.no_scaled:
         out["hash_match"] = scaled_hash_match(torch, aibx, args.config, step, 4 << 20)
         out["hash_match_blocks_per_s"] = out["hash_match"]["blocks_per_s"]

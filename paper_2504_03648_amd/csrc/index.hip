@@ -161,7 +161,9 @@ __global__ __launch_bounds__(kIndexThreads) void index_insert_kernel(
     u64 cand_bucket = 0, cand_probes = 0;
     int cand_sub = 0;               // group-uniform
     u64 cand_expected = 0;          // valid in lane cand_sub
-    u64 guard = 2 * n_buckets + 4096;  // hard bound on loop trips; never reached in practice
+    // Proven bound on loop trips: a scan visits at most n_buckets buckets, and a scan is repeated
+    // only after a lost claim, i.e. after some other insert filled a slot (at most n_slots times).
+    u64 guard = n_buckets > (1ull << 30) ? ~0ull : n_buckets * (n_buckets * kBucket + 1);
     while (__any(active)) {
       u64* slot = t.slots + 2 * (b * kBucket + sub);
       const u64 seen = active ? load_key_fresh(slot) : kEmpty;

@@ -77,9 +77,12 @@ class HipIndex:
         self.c_ev = torch.zeros(2, dtype=torch.int64, device="cuda")
 
     def __del__(self):
-        if getattr(self, "h", None) is not None:
-            self.a.aibx_index_destroy(self.h)
-            self.h = None
+        try:
+            if getattr(self, "h", None) is not None:
+                self.a.aibx_index_destroy(self.h)
+                self.h = None
+        except Exception:          # interpreter shutdown: the binding may already be gone
+            pass
 
     def _dev(self, x, dtype=np.uint64):
         x = np.ascontiguousarray(x, dtype=dtype)

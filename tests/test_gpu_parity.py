@@ -77,9 +77,13 @@ def _same_bucket_keys(rng, n_slots, n):
     return np.concatenate([pick[: n // 2], keys[: n - min(len(pick), n // 2)]])
 
 
-@pytest.mark.parametrize("n_slots", [8, 16, 64, 1024])
-def test_index_random_ops_against_oracle(n_slots):
-    rng = np.random.default_rng(n_slots)
+@pytest.mark.parametrize("n_slots,seed", [(8, 0), (16, 0), (64, 0), (64, 1), (1024, 0), (1024, 1),
+                                           (1024, 2), (1024, 3), (1024, 4), (1024, 5)])
+def test_index_random_ops_against_oracle(n_slots, seed):
+    """Random batches against the oracle's map. Half of the keys share two home buckets, so probe
+    sequences run long, wrap around the table, and many concurrent inserts fight for the same
+    tombstones (an insert that loses a claim must rescan, however often that happens)."""
+    rng = np.random.default_rng(n_slots * 100 + seed)
     gi, oi = HipIndex(n_slots), oracle.Index(n_slots)
     universe = np.unique(_same_bucket_keys(rng, n_slots, 3 * n_slots))
     for step in range(120):
