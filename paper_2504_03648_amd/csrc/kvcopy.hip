@@ -20,8 +20,6 @@ namespace {
 struct CopyArgs {
   unsigned char* pool;
   unsigned char* staging;
-  const int32_t* page_ids;
-  const int32_t* slot_ids;   // nullable
   u64* bad_page;             // nullable
   u64 seg_stride, page_stride, seg_bytes, staging_stride;
   int64_t n, n_pages;
@@ -34,22 +32,29 @@ struct CopyArgs {
 
 typedef __attribute__((ext_vector_type(4))) u32 vec16;
 
+// The asm statements below carry no "memory" clobber on purpose: they are volatile (kept, and kept
+// in order), the data dependence orders each store after its load, and without the clobber the
+// compiler may fetch the page and slot ids with scalar loads issued together, which shortens the
+// dependent latency in front of every tile.
 __device__ __forceinline__ vec16 load_stream(const void* p) {
   vec16 v;
-  asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(v) : "v"(p) : "memory");
+  asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(v) : "v"(p));
   return v;
 }
-__device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(0)"); }
 __device__ __forceinline__ void store_stream(void* p, vec16 v) {
-  asm volatile("global_store_dwordx4 %0, %1, off nt" ::"v"(p), "v"(v) : "memory");
+  asm volatile("global_store_dwordx4 %0, %1, off nt" ::"v"(p), "v"(v));
 }
 __device__ __forceinline__ void store_through(void* p, vec16 v) {
-  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(v) : "memory");
+  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(v));
 }
 
 template <bool kGather>
-__device__ __forceinline__ void copy_tile(const CopyArgs& a, int64_t i, u32 tile_in_block, u32 threads) {
-  const int64_t p = a.page_ids[i];
+__device__ __forceinline__ void copy_tile(const CopyArgs& a, const int32_t* __restrict__ page_ids,
+                                          const int32_t* __restrict__ slot_ids, int64_t i, u32 tile_in_block,
+                                          u32 threads) {
+  const int64_t p = page_ids[i];
+  const int64_t q = slot_ids ? (int64_t)slot_ids[i] : i;  // fetched together with the page id
   if (p < 0) return;  // hole
   if (p >= a.n_pages) {
     if (tile_in_block == 0 && threadIdx.x == 0 && a.bad_page) atomicAdd((unsigned long long*)a.bad_page, 1ull);
@@ -59,7 +64,6 @@ __device__ __forceinline__ void copy_tile(const CopyArgs& a, int64_t i, u32 tile
   const u32 c = tile_in_block - s * a.chunks_per_seg;
   const u64 off = ((u64)c * threads + threadIdx.x) * 16;
   if (off >= a.seg_bytes) return;  // ragged last chunk of a segment
-  const int64_t q = a.slot_ids ? (int64_t)a.slot_ids[i] : i;
   unsigned char* in_pool = a.pool + (u64)s * a.seg_stride + (u64)p * a.page_stride + off;
   unsigned char* in_stage = a.staging + (u64)q * a.staging_stride + (u64)s * a.seg_bytes + off;
   if (kGather) {
@@ -73,19 +77,21 @@ __device__ __forceinline__ void copy_tile(const CopyArgs& a, int64_t i, u32 tile
   }
 }
 
-// x = tile inside the block, y = entry (strided when n exceeds the y limit of a grid)
+// x = tile inside the block, y = entry relative to first_entry
 template <bool kGather, int kThreads>
-__global__ __launch_bounds__(kThreads) void kv_copy_2d_kernel(CopyArgs a) {
-  for (int64_t i = blockIdx.y; i < a.n; i += gridDim.y) copy_tile<kGather>(a, i, blockIdx.x, kThreads);
+__global__ __launch_bounds__(kThreads) void kv_copy_2d_kernel(CopyArgs a, const int32_t* __restrict__ page_ids,
+                                                              const int32_t* __restrict__ slot_ids) {
+  copy_tile<kGather>(a, page_ids, slot_ids, a.first_entry + blockIdx.y, blockIdx.x, kThreads);
 }
 
 // XCD x (= workgroup id mod 8) takes tiles [x*tiles_per_xcd, (x+1)*tiles_per_xcd)
 template <bool kGather, int kThreads>
-__global__ __launch_bounds__(kThreads) void kv_copy_xcd_kernel(CopyArgs a) {
+__global__ __launch_bounds__(kThreads) void kv_copy_xcd_kernel(CopyArgs a, const int32_t* __restrict__ page_ids,
+                                                               const int32_t* __restrict__ slot_ids) {
   const u32 t = (blockIdx.x & 7u) * a.tiles_per_xcd + (blockIdx.x >> 3);
-  if ((blockIdx.x >> 3) >= a.tiles_per_xcd || t >= a.total_tiles) return;
+  if (t >= a.total_tiles) return;
   const u32 i = t / a.tiles_per_block;
-  copy_tile<kGather>(a, a.first_entry + i, t - i * a.tiles_per_block, kThreads);
+  copy_tile<kGather>(a, page_ids, slot_ids, a.first_entry + i, t - i * a.tiles_per_block, kThreads);
 }
 
 template <bool kGather>
@@ -115,8 +121,6 @@ int launch_copy(const aibx_pool_desc* pool, const int32_t* d_page_ids, const int
   CopyArgs a;
   a.pool = static_cast<unsigned char*>(pool->base);
   a.staging = static_cast<unsigned char*>(d_staging);
-  a.page_ids = d_page_ids;
-  a.slot_ids = d_slot_ids;
   a.bad_page = d_bad;
   a.seg_stride = pool->seg_stride;
   a.page_stride = pool->page_stride;
@@ -130,9 +134,14 @@ int launch_copy(const aibx_pool_desc* pool, const int32_t* d_page_ids, const int
   a.total_tiles = a.tiles_per_xcd = 0;
   hipStream_t st = as_stream(stream);
   if (use_2d) {
-    dim3 grid((u32)tpb, (u32)(n < 65535 ? n : 65535));
-    kv_copy_2d_kernel<kGather, 128><<<grid, 128, 0, st>>>(a);
-    return launch_status();
+    for (int64_t first = 0; first < n; first += 65535) {  // grid y limit
+      const int64_t n_here = (n - first) < 65535 ? (n - first) : 65535;
+      a.first_entry = first;
+      kv_copy_2d_kernel<kGather, 128><<<dim3((u32)tpb, (u32)n_here), 128, 0, st>>>(a, d_page_ids, d_slot_ids);
+      const int rc = launch_status();
+      if (rc != AIBX_OK) return rc;
+    }
+    return AIBX_OK;
   }
   // split so that one launch has fewer than 2^31 tiles
   const int64_t max_entries = (int64_t)(0x7FFFFFF0ull / tpb);
@@ -141,7 +150,7 @@ int launch_copy(const aibx_pool_desc* pool, const int32_t* d_page_ids, const int
     a.first_entry = first;
     a.total_tiles = (u32)((u64)n_here * tpb);
     a.tiles_per_xcd = (a.total_tiles + 7) / 8;
-    kv_copy_xcd_kernel<kGather, 256><<<dim3(a.tiles_per_xcd * 8), 256, 0, st>>>(a);
+    kv_copy_xcd_kernel<kGather, 256><<<dim3(a.tiles_per_xcd * 8), 256, 0, st>>>(a, d_page_ids, d_slot_ids);
     const int rc = launch_status();
     if (rc != AIBX_OK) return rc;
   }
