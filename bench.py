@@ -33,7 +33,8 @@ NO_VALUE = np.uint64(0xFFFFFFFFFFFFFFFF)
 
 # HBM bytes per gather launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the same
 # counters on a plain copy of known size; valid only for the kernel source it was taken on.
-MEASURED_TRAFFIC = {"kvcopy_sha1": None, "bytes_per_launch": None}
+MEASURED_TRAFFIC = {"kvcopy_sha1": "3f3b9d6e33979471c67686c6c4953e7899ddcb89",
+                    "bytes_per_launch": 18874972 * 1024}
 
 
 def _u64(t):
