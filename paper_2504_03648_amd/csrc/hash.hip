@@ -2,7 +2,7 @@
 // routing, Section 3.2.2, and its cross-request KV reuse, Section 3.2.5). The definition is in
 // aibx.h; this file evaluates it on the GPU.
 //
-// Layout of the work: one workgroup of kHashWaves wavefronts per request. A wavefront takes a
+// Layout of the work: one workgroup of 4 wavefronts (or, for large batches, 1) per request. A wavefront takes a
 // tile of 1024 consecutive tokens (64 coalesced tokens per load, 16 loads in flight), so a lane
 // always sees the same position-in-block and folds its position constant once. The per-block sums
 // are formed by a transposing butterfly across the lanes that share a block, the block digests
@@ -18,7 +18,7 @@ constexpr u64 K1 = 0x6A09E667F3BCC909ull;
 constexpr u64 K2 = 0xBB67AE8584CAA73Bull;
 constexpr u64 K3 = 0x3C6EF372FE94F82Bull;
 
-constexpr int kHashWaves = 4;
+constexpr int kGeneralWaves = 4;  // wavefronts per request on the general path
 constexpr int kTileTokens = 1024;  // tokens per wavefront tile
 constexpr int kLoads = kTileTokens / kWave;
 
@@ -80,7 +80,7 @@ __device__ __forceinline__ u64 chain_scan(u64 d, int lane) {
 }
 
 // ---- fast path: block sizes 16, 32, 64 -------------------------------------------------------
-template <int kB>
+template <int kB, int kHashWaves>
 __global__ __launch_bounds__(kHashWaves* kWave) void block_hash_pow2_kernel(
     const int32_t* __restrict__ tokens, const int64_t* __restrict__ tok_off,
     const int64_t* __restrict__ blk_off, u64 seed, u64* __restrict__ hash_out) {
@@ -179,6 +179,11 @@ __global__ __launch_bounds__(kHashWaves* kWave) void block_hash_pow2_kernel(
     const u64 local = chain_scan<kNB>(d, lane);
     // tile aggregate = scan value at the tile's last block (earlier tiles are always full)
     const u64 aggr = shfl64(local, kNB - 1);
+    if (kHashWaves == 1) {  // one wavefront per request: the carry stays in registers
+      if (valid) out[jb] = out_hash(carry_w * carry + local);
+      carry = ipow(K2, kNB) * carry + aggr;
+      continue;
+    }
     if (lane == 0) lds_aggr[parity][wave] = aggr;
     __syncthreads();
     u64 cin = carry;
@@ -193,7 +198,7 @@ __global__ __launch_bounds__(kHashWaves* kWave) void block_hash_pow2_kernel(
 // ---- general path: any block size in [1, 1024] ------------------------------------------------
 // Phase 1: each wavefront reduces whole blocks to digests and parks them in hash_out.
 // Phase 2: wavefront 0 runs the chain over the request's digests, 64 blocks at a time.
-__global__ __launch_bounds__(kHashWaves* kWave) void block_hash_general_kernel(
+__global__ __launch_bounds__(kGeneralWaves* kWave) void block_hash_general_kernel(
     const int32_t* __restrict__ tokens, const int64_t* __restrict__ tok_off,
     const int64_t* __restrict__ blk_off, int block_size, u64 seed, u64* __restrict__ hash_out) {
   const int r = blockIdx.x;
@@ -204,7 +209,7 @@ __global__ __launch_bounds__(kHashWaves* kWave) void block_hash_general_kernel(
   if (n_r <= 0) return;
   const int32_t* tok = tokens + tok_off[r];
   u64* out = hash_out + b0;
-  for (int64_t j = wave; j < n_r; j += kHashWaves) {
+  for (int64_t j = wave; j < n_r; j += kGeneralWaves) {
     const int32_t* blk = tok + j * block_size;
     u64 c = 0;
     for (int i = lane; i < block_size; i += kWave) {
@@ -250,13 +255,23 @@ extern "C" int aibx_block_hash(const int32_t* d_tokens, const int64_t* d_tok_off
   if (!aligned(d_tokens, 4) || !aligned(d_tok_off, 8) || !aligned(d_blk_off, 8) || !aligned(d_hash_out, 8))
     return AIBX_ERR_ALIGN;
   hipStream_t st = as_stream(stream);
-  dim3 grid((u32)n_req), block(kHashWaves * kWave);
+  // Thousands of requests: one wavefront each (no barrier, nothing idles on short requests).
+  // Few requests: four wavefronts each, so that a small batch finishes in fewer serial tiles.
+  const bool wide = n_req < 4096;
+  dim3 grid((u32)n_req);
+#define AIBX_LAUNCH_HASH(B)                                                                              \
+  if (wide)                                                                                              \
+    block_hash_pow2_kernel<B, 4><<<grid, 4 * kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off, seed, d_hash_out); \
+  else                                                                                                   \
+    block_hash_pow2_kernel<B, 1><<<grid, kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off, seed, d_hash_out)
   switch (block_size) {
-    case 16: block_hash_pow2_kernel<16><<<grid, block, 0, st>>>(d_tokens, d_tok_off, d_blk_off, seed, d_hash_out); break;
-    case 32: block_hash_pow2_kernel<32><<<grid, block, 0, st>>>(d_tokens, d_tok_off, d_blk_off, seed, d_hash_out); break;
-    case 64: block_hash_pow2_kernel<64><<<grid, block, 0, st>>>(d_tokens, d_tok_off, d_blk_off, seed, d_hash_out); break;
+    case 16: AIBX_LAUNCH_HASH(16); break;
+    case 32: AIBX_LAUNCH_HASH(32); break;
+    case 64: AIBX_LAUNCH_HASH(64); break;
     default:
-      block_hash_general_kernel<<<grid, block, 0, st>>>(d_tokens, d_tok_off, d_blk_off, block_size, seed, d_hash_out);
+      block_hash_general_kernel<<<grid, kGeneralWaves * kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off, block_size,
+                                                                        seed, d_hash_out);
   }
+#undef AIBX_LAUNCH_HASH
   return launch_status();
 }

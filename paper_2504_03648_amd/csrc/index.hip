@@ -4,14 +4,16 @@
 //
 // Table: open addressing over buckets of 8 slots; a slot is {u64 key, u64 value}, so a bucket is
 // one 128-byte line. Key 0 = EMPTY, key 2^64-1 = TOMBSTONE. A key lives in the first bucket of
-// its probe sequence (home, home+1, ... mod n_buckets) that had a free slot when it was inserted.
+// its probe sequence (home, home+step, home+2*step, ... mod n_buckets, step odd and key-dependent)
+// that had a free slot when it was inserted.
 // Invariant kept by every kernel: a probe sequence continues past a bucket only if that bucket
 // has no EMPTY slot; so a lookup stops at the first bucket that has one.
 //
-// Execution shape: 8 lanes cooperate on one key - each reads one 16-byte slot, the 8 reads are one
-// coalesced 128-byte line - and a wavefront keeps 8 keys (8 lines) in flight per step. A
-// wavefront owns 64 consecutive keys, loads them coalesced, and hands key 8g+r to lane group g in
-// step r through cross-lane reads.
+// Execution shape. Lookups (prefix match): one lane per key, the lane reads the whole bucket.
+// Updates (insert, evict): 8 lanes cooperate on one key - each reads one 16-byte slot, the 8 reads
+// are one coalesced 128-byte line - so that the group can agree on the slot to claim; a wavefront
+// owns 64 consecutive keys, loads them coalesced, and hands key 8g+r to lane group g in step r
+// through cross-lane reads.
 #include "common.h"
 
 struct aibx_index {
@@ -27,7 +29,10 @@ namespace {
 constexpr u64 kEmpty = AIBX_KEY_EMPTY;
 constexpr u64 kTomb = AIBX_KEY_TOMBSTONE;
 constexpr u64 kNoValue = AIBX_NO_VALUE;
-constexpr int kBucket = 8;                       // slots per bucket = lanes per key
+#ifndef AIBX_BUCKET_SLOTS
+#define AIBX_BUCKET_SLOTS 8
+#endif
+constexpr int kBucket = AIBX_BUCKET_SLOTS;       // slots per bucket = lanes per key (4 or 8)
 constexpr u64 kHomeMul = 0x9E3779B97F4A7C15ull;  // multiplicative (Fibonacci) bucket hash
 constexpr int kIndexThreads = 256;
 constexpr int kWavesPerGroup = kIndexThreads / kWave;
@@ -42,6 +47,12 @@ __device__ __forceinline__ u64 home_bucket(const Table& t, u64 key) {
   return t.shift >= 64 ? 0ull : (key * kHomeMul) >> t.shift;
 }
 
+// Double hashing over buckets: the k-th bucket of a key's probe sequence is home + k*step with an
+// odd step taken from other bits of the key's product, so full buckets do not cluster the way they
+// do under linear probing (which buys nothing here: a neighbouring line costs as much as any other).
+// An odd step modulo a power of two visits every bucket once.
+__device__ __forceinline__ u64 probe_step(u64 key) { return ((key * kHomeMul) >> 7) | 1ull; }
+
 __device__ __forceinline__ u64 shfl64(u64 v, int src) {
   u32 lo = (u32)v, hi = (u32)(v >> 32);
   lo = __shfl(lo, src);
@@ -51,7 +62,7 @@ __device__ __forceinline__ u64 shfl64(u64 v, int src) {
 
 // The 8 bits of a wavefront-wide ballot that belong to this lane's group.
 __device__ __forceinline__ u32 group_bits(bool pred, int group) {
-  return (u32)(__ballot(pred) >> (group * kBucket)) & 0xFFu;
+  return (u32)(__ballot(pred) >> (group * kBucket)) & ((1u << kBucket) - 1u);
 }
 
 __device__ __forceinline__ u64 load_key_fresh(const u64* p) {
@@ -61,50 +72,41 @@ __device__ __forceinline__ u64 load_key_fresh(const u64* p) {
 typedef __attribute__((ext_vector_type(2))) u64 slot_t;  // .x = key, .y = value
 
 // ---- lookup ------------------------------------------------------------------------------------
-// Looks up the wavefront's 64 keys (lane l holds key l; `n_valid` of them are real). Returns in
-// lane l the value of key l or kNoValue. Read-only: plain cached loads.
-__device__ __forceinline__ u64 lookup64(const Table& t, u64 my_key, int n_valid, int lane) {
-  const int group = lane / kBucket, sub = lane % kBucket;
-  u64 key[kBucket];
-  slot_t slot[kBucket];
-  u64 bucket[kBucket];
+// One lane per key: the lane reads its key's whole bucket (8 x 16 bytes, one 128-byte line) and
+// compares the 8 keys itself. Random line reads on this GPU are bound by the number of lines
+// requested (about 55-80 G lines/s whether a line is fetched by one lane or by eight), so this
+// costs the memory system no more than a cooperative read and needs no cross-lane work at all.
+// Read-only: plain cached loads. Returns the key's value or kNoValue.
+__device__ __forceinline__ u64 lookup_one(const Table& t, u64 key, bool valid) {
+  u64 result = kNoValue;
+  bool open = valid && key != kEmpty && key != kTomb;
+  u64 b = home_bucket(t, key);
+  const u64 step = probe_step(key);
+  for (u64 seen_buckets = 0; open; ++seen_buckets) {
+    const slot_t* bucket = reinterpret_cast<const slot_t*>(t.slots + 2 * b * kBucket);
+    slot_t s[kBucket];
 #pragma unroll
-  for (int r = 0; r < kBucket; ++r) {  // 8 independent line reads in flight
-    key[r] = shfl64(my_key, group * kBucket + r);
-    bucket[r] = home_bucket(t, key[r]);
-    const bool live = group * kBucket + r < n_valid && key[r] != kEmpty && key[r] != kTomb;
-    slot[r] = live ? *reinterpret_cast<const slot_t*>(t.slots + 2 * (bucket[r] * kBucket + sub))
-                   : slot_t{kEmpty, 0};
-  }
-  u64 my_value = kNoValue;
+    for (int j = 0; j < kBucket; ++j) s[j] = bucket[j];
+    bool ends = seen_buckets >= t.bucket_mask;  // that was the last bucket of the table
 #pragma unroll
-  for (int r = 0; r < kBucket; ++r) {
-    const bool live = group * kBucket + r < n_valid && key[r] != kEmpty && key[r] != kTomb;
-    u32 hit = group_bits(live && slot[r].x == key[r], group);
-    u32 empty = group_bits(!live || slot[r].x == kEmpty, group);
-    u64 b = bucket[r];
-    slot_t s = slot[r];
-    u64 probes = 1;
-    // rare: the home bucket is full of other keys - walk on (wavefront-uniform loop)
-    while (__any(hit == 0 && empty == 0 && probes <= t.bucket_mask)) {
-      const bool walk = hit == 0 && empty == 0 && probes <= t.bucket_mask;
-      if (walk) {
-        b = (b + 1) & t.bucket_mask;
-        s = *reinterpret_cast<const slot_t*>(t.slots + 2 * (b * kBucket + sub));
-        ++probes;
+    for (int j = 0; j < kBucket; ++j) {
+      if (s[j].x == key) {
+        result = s[j].y;
+        ends = true;
       }
-      const u32 h2 = group_bits(walk && s.x == key[r], group);
-      const u32 e2 = group_bits(walk && s.x == kEmpty, group);
-      if (walk) { hit = h2; empty = e2; }
+      ends |= s[j].x == kEmpty;  // a bucket with an EMPTY slot ends the probe sequence
     }
-    const int hit_lane = group * kBucket + (hit ? __ffs(hit) - 1 : 0);
-    const u64 v = shfl64(s.y, hit_lane);
-    if (sub == r) my_value = hit ? v : kNoValue;
+    open = !ends;
+    b = (b + step) & t.bucket_mask;
   }
-  return my_value;
+  return result;
 }
 
-// One workgroup per request; wavefront w takes the request's blocks [64(w+4k), 64(w+4k)+64).
+// One workgroup of 4 wavefronts per request; wavefront w takes the request's blocks
+// [64(w + 4k), +64) and requests the next tile's keys while this tile's buckets are in flight.
+// Measured alternatives that lost: one wavefront per request (-20 %: long requests serialise),
+// a flat pass over all blocks plus a first-miss pass (-15 %: second launch, values re-read), and
+// lanes that refill themselves with their next key (no gain: the bound is lines requested).
 __global__ __launch_bounds__(kIndexThreads) void prefix_match_kernel(
     Table t, const u64* __restrict__ hashes, const int64_t* __restrict__ blk_off,
     u64* __restrict__ values_out, int32_t* __restrict__ match_len) {
@@ -114,13 +116,15 @@ __global__ __launch_bounds__(kIndexThreads) void prefix_match_kernel(
   const int64_t b0 = blk_off[r];
   const int64_t n_r = blk_off[r + 1] - b0;
   int64_t first_miss = n_r;
-  for (int64_t base = (int64_t)wave * kWave; base < n_r; base += kIndexThreads) {
-    const int64_t left = n_r - base;
-    const int n_valid = left < kWave ? (int)left : kWave;
-    const u64 k = lane < n_valid ? hashes[b0 + base + lane] : kEmpty;
-    const u64 v = lookup64(t, k, n_valid, lane);
-    if (lane < n_valid && values_out) values_out[b0 + base + lane] = v;
-    const u64 miss = __ballot(lane < n_valid && v == kNoValue);
+  int64_t base = (int64_t)wave * kWave;
+  u64 k_next = base + lane < n_r ? hashes[b0 + base + lane] : kEmpty;
+  for (; base < n_r; base += kIndexThreads) {
+    const bool valid = base + lane < n_r;
+    const u64 k = k_next;
+    k_next = base + kIndexThreads + lane < n_r ? hashes[b0 + base + kIndexThreads + lane] : kEmpty;
+    const u64 v = lookup_one(t, k, valid);
+    if (valid && values_out) values_out[b0 + base + lane] = v;
+    const u64 miss = __ballot(valid && v == kNoValue);
     if (miss && first_miss == n_r) first_miss = base + (__ffsll((unsigned long long)miss) - 1);
   }
   if (lane == 0) lds_first[wave] = (int)first_miss;
@@ -155,6 +159,7 @@ __global__ __launch_bounds__(kIndexThreads) void index_insert_kernel(
     bool active = real && key != kEmpty && key != kTomb;
     if (real && !active) ++n_full;  // reserved key: dropped
     u64 b = home_bucket(t, key);
+    const u64 step = probe_step(key);
     u64 probes = 0;                 // buckets fully scanned so far
     // candidate free slot (first in probe order); kept by the lane that owns it
     bool have_cand = false;         // group-uniform
@@ -187,7 +192,7 @@ __global__ __launch_bounds__(kIndexThreads) void index_insert_kernel(
             if (sub == cand_sub) cand_expected = seen;
           }
           if (!chain_ends) {
-            b = (b + 1) & t.bucket_mask;
+            b = (b + step) & t.bucket_mask;
             ++probes;
           } else if (!have_cand) {
             ++n_full;  // every slot of the table is taken
@@ -263,6 +268,7 @@ __global__ __launch_bounds__(kIndexThreads) void index_evict_kernel(
     bool active = real && key != kEmpty && key != kTomb;
     if (real && !active) ++n_miss;
     u64 b = home_bucket(t, key);
+    const u64 step = probe_step(key);
     u64 probes = 0;
     u64 result = kNoValue;  // group-uniform
     while (__any(active)) {
@@ -290,7 +296,7 @@ __global__ __launch_bounds__(kIndexThreads) void index_evict_kernel(
           ++n_miss;
           active = false;
         } else {
-          b = (b + 1) & t.bucket_mask;
+          b = (b + step) & t.bucket_mask;
           ++probes;
         }
       }

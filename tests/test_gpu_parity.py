@@ -55,6 +55,73 @@ def test_block_hash_configs_full_size(hip, cfg):
     assert np.array_equal(got, want)
 
 
+@pytest.mark.parametrize("B", [16, 32, 64])
+def test_block_hash_many_requests(hip, B):
+    """Thousands of requests take the one-wavefront-per-request launch: carry in registers,
+    several tiles per wavefront, ragged tails."""
+    rng = np.random.default_rng(7 * B)
+    tok, tok_off, lens = _ragged(rng, 5000, 0, 40 * B)
+    lens[11] = 9000 + B // 3                      # a long request among the short ones
+    np.cumsum(lens, out=tok_off[1:])
+    tok = rng.integers(0, 32000, size=int(tok_off[-1]), dtype=np.int32)
+    blk_off = np.zeros(len(lens) + 1, dtype=np.int64)
+    np.cumsum(lens // B, out=blk_off[1:])
+    want = oracle.block_hash(tok, tok_off, blk_off, B, 3)
+    got = hip.block_hash(tok, tok_off, blk_off, B, 3)
+    assert np.array_equal(got, want)
+
+
+def test_match_many_requests():
+    """Thousands of short ragged requests in one call."""
+    rng = np.random.default_rng(5)
+    keys = np.unique(rng.integers(1, 2**63, size=60000, dtype=np.uint64))
+    gi, oi = HipIndex(1 << 16), oracle.Index(1 << 16)
+    present = keys[: len(keys) // 2]
+    for ix in (gi, oi):
+        ix.insert(present, present >> np.uint64(7))
+    sizes = rng.integers(0, 200, size=5000)
+    sizes[17] = 1000
+    blk_off = np.zeros(len(sizes) + 1, dtype=np.int64)
+    np.cumsum(sizes, out=blk_off[1:])
+    h = rng.choice(keys, size=int(blk_off[-1]))
+    lead = rng.random(len(h)) < 0.9                 # mostly present keys, so matches run long
+    h[lead] = rng.choice(present, size=int(lead.sum()))
+    gv, gm = gi.match(h, blk_off)
+    ov, om = oi.match(h, blk_off)
+    assert np.array_equal(gv, ov) and np.array_equal(gm, om)
+    assert om.max() > 64
+
+
+@pytest.mark.parametrize("n_blocks", [(1 << 17) + 777, (1 << 20) + 333, (1 << 22) + 5])
+def test_match_large_batches(n_blocks):
+    """Batches of 2^17 to 2^22 blocks over thousands of ragged requests; a table at load 0.75
+    with tombstones gives long probe sequences."""
+    rng = np.random.default_rng(n_blocks)
+    n_slots = 1 << 16
+    keys = np.unique(rng.integers(1, 2**63, size=80000, dtype=np.uint64))
+    present = keys[: int(n_slots * 0.75)]
+    gi, oi = HipIndex(n_slots), oracle.Index(n_slots)
+    for ix in (gi, oi):
+        ix.insert(present, present ^ np.uint64(0x55))
+    dropped = present[::9]
+    assert np.array_equal(gi.evict(dropped), oi.evict(dropped))      # leaves tombstones behind
+    sizes = rng.integers(0, 600, size=n_blocks // 300 + 1)
+    sizes[-1] += n_blocks - sizes.sum() if sizes.sum() < n_blocks else 0
+    sizes = sizes[np.cumsum(sizes) <= n_blocks]
+    sizes = np.append(sizes, n_blocks - sizes.sum())
+    blk_off = np.zeros(len(sizes) + 1, dtype=np.int64)
+    np.cumsum(sizes, out=blk_off[1:])
+    h = rng.choice(keys, size=n_blocks)
+    lead = rng.random(n_blocks) < 0.97
+    h[lead] = rng.choice(present, size=int(lead.sum()))
+    h[5] = 0
+    h[6] = NO                                                        # reserved keys read as absent
+    gv, gm = gi.match(h, blk_off)
+    ov, om = oi.match(h, blk_off)
+    assert np.array_equal(gv, ov) and np.array_equal(gm, om)
+    assert om.max() >= 8
+
+
 def test_block_hash_golden_vector_and_empty(hip):
     t = np.arange(32, dtype=np.int32)
     got = hip.block_hash(t, [0, 32], [0, 2], 16, 0)
@@ -73,7 +140,7 @@ def _same_bucket_keys(rng, n_slots, n):
     if lg == 0:
         return keys[:n]
     home = (keys * np.uint64(0x9E3779B97F4A7C15)) >> np.uint64(64 - lg)
-    pick = keys[(home == home[0]) | (home == (home[0] + np.uint64(1)) % np.uint64(nb))]
+    pick = keys[(home == home[0]) | (home == (home[0] + np.uint64(1)) % np.uint64(nb))]   # two home buckets
     return np.concatenate([pick[: n // 2], keys[: n - min(len(pick), n // 2)]])
 
 
