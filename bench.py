@@ -2,11 +2,12 @@
 """Benchmark of the KV-cache hot path on one MI355X.
 
 A step is one pass of the whole path over the Llama-3-8B-shaped workload (64 requests x 4096
-tokens, 16-token blocks, 20,000-page pool of 2 MiB blocks in 64 planes, 2^20-slot index at load
-0.5): clear + preload the index, hash every request, index every block, gather the cold half of
-the resident blocks to staging (offload), re-point and evict index entries, match every request,
-scatter the matched staged blocks back into the pool (onload), update the index. Every array the
-step reads is resident in HBM before the clock starts.
+tokens, 16-token blocks, 20,000-page pool of 2 MiB blocks in 64 planes, 2^20-slot index preloaded
+to load 0.5): hash every request, index every block, gather the cold half of the resident blocks
+to staging (offload), re-point and evict index entries, match every request, scatter the matched
+staged blocks back into the pool (onload), update the index, and evict the batch's keys again so
+that the next step starts from the same index. Every array the step reads is resident in HBM
+before the clock starts.
 
 Prints ONE JSON line. `value` = bytes read + written by the gathers and scatters of a step divided
 by the whole step's time. `roofline` is the gather kernel against 8 TB/s. `hash_match` is the
@@ -104,7 +105,9 @@ class Step:
         self.ev_out = torch.empty(len(dropped), dtype=torch.int64, device=dev)
         # run the index part once to learn which staged blocks are on a matched prefix
         self.n_on = 0
-        self._index_front()
+        self.all_keys = _dev_u64(torch, dkeys)
+        self.preload()
+        self._front()
         aibx.aibx_prefix_match(self.ix, self.hash, self.blk_off, self.R, self.N, self.values, self.mlen)
         values, mlen = _u64(self.values), self.mlen.cpu().numpy()
         on_prefix = np.zeros(self.N, dtype=bool)
@@ -123,13 +126,19 @@ class Step:
         self.copy_bytes = 2 * (self.n_cold + self.n_on) * g.blk_bytes
         self.gather_bytes = 2 * self.n_cold * g.blk_bytes
         self.ev_g0 = self.ev_g1 = None
+        self.preload()            # the planning pass left the batch's keys in the index
         torch.cuda.synchronize()
 
-    def _index_front(self):
+    def preload(self):
+        """Index state every step starts from: empty table plus the filler keys (load factor)."""
+        a = self.a
+        a.aibx_index_clear(self.ix)
+        a.aibx_index_insert(self.ix, self.fk, self.fv, self.fk.numel(), self.counters[0:3])
+
+    def _front(self):
+        """Hash, index every block, offload the cold blocks, re-point and evict their entries."""
         a, wl = self.a, self.wl
         c = self.counters
-        a.aibx_index_clear(self.ix)
-        a.aibx_index_insert(self.ix, self.fk, self.fv, self.fk.numel(), c[0:3])
         a.aibx_block_hash(self.tokens, self.tok_off, self.blk_off, self.R, self.N, wl.block_size,
                           wl.hash_seed, self.hash)
         a.aibx_index_insert(self.ix, self.hash, self.block_values, self.N, c[0:3])
@@ -143,13 +152,16 @@ class Step:
         a.aibx_index_evict(self.ix, self.dropped, self.dropped.numel(), self.ev_out, c[3:5])
 
     def run(self, events=None):
+        """One step, enqueued on the current stream. It ends by evicting the batch's own keys, so
+        the index is back to the preloaded state (fillers only) for the next step."""
         a, wl = self.a, self.wl
         self.ev_g0, self.ev_g1 = events if events else (None, None)
-        self._index_front()
+        self._front()
         a.aibx_prefix_match(self.ix, self.hash, self.blk_off, self.R, self.N, self.values, self.mlen)
         a.aibx_kv_scatter(self.desc, self.on_pages, self.on_slots, self.n_on, self.staging,
-                          wl.geom.blk_bytes, self.counters[5:6])
+                          wl.geom.blk_bytes, self.counters[6:7])
         a.aibx_index_insert(self.ix, self.on_keys, self.on_vals, self.n_on, self.counters[0:3])
+        a.aibx_index_evict(self.ix, self.all_keys, self.all_keys.numel(), None, self.counters[3:5])
 
 
 def time_calls(torch, fn, reps, warm=2):
