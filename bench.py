@@ -34,8 +34,8 @@ NO_VALUE = np.uint64(0xFFFFFFFFFFFFFFFF)
 
 # HBM bytes per gather launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the same
 # counters on a plain copy of known size; valid only for the kernel source it was taken on.
-MEASURED_TRAFFIC = {"kvcopy_sha1": "3f3b9d6e33979471c67686c6c4953e7899ddcb89",
-                    "bytes_per_launch": 18874972 * 1024}
+MEASURED_TRAFFIC = {"kvcopy_sha1": "096328e16844ccbf510eb5efa6d79c5528e6755f",
+                    "bytes_per_launch": 19327169539}
 
 
 def _u64(t):
@@ -241,6 +241,113 @@ def cpu_baseline(wl, gpu_hash, gpu_mlen_fn):
     }
 
 
+def survey_config(torch, aibx, cfg, layout=None):
+    """Per-config figures (not the headline line): copy bandwidth of one gather and one scatter
+    batch at the config's geometry, two-stream gather+scatter, native-size call latencies, the
+    scaled hash+match batch, and index update rates. Returns a dict."""
+    from workloads import fill_pool_torch, filler_keys, make_scaled_tokens, make_workload
+    wl = make_workload(cfg, "full", layout=layout)
+    g = wl.geom
+    out = {"config": cfg, "name": wl.name, "layout": g.layout, "n_seg": g.n_seg, "seg_bytes": g.seg_bytes,
+           "blk_bytes": g.blk_bytes, "pool_GiB": g.pool_bytes / 2**30}
+    n = min(wl.batch_pages, g.n_pages // 2)
+    pool = torch.empty(g.pool_bytes, dtype=torch.uint8, device="cuda")
+    fill_pool_torch(pool, wl.kv_dtype, cfg)
+    staging = torch.empty(2 * n * g.blk_bytes, dtype=torch.uint8, device="cuda")
+    desc = aibx.make_pool_desc(pool, *g.as_tuple())
+    rng = np.random.default_rng(cfg)
+    perm = rng.permutation(g.n_pages).astype(np.int32)
+    pa, pb = torch.from_numpy(perm[:n].copy()).cuda(), torch.from_numpy(perm[n:2 * n].copy()).cuda()
+    sa = torch.arange(n, dtype=torch.int32, device="cuda")
+    sb = torch.arange(n, 2 * n, dtype=torch.int32, device="cuda")
+    traffic = 2 * n * g.blk_bytes
+    ms, _ = time_calls(torch, lambda: aibx.aibx_kv_gather(desc, pa, sa, n, staging, g.blk_bytes), 7)
+    out["gather_GBps"] = traffic / ms / 1e6
+    ms, _ = time_calls(torch, lambda: aibx.aibx_kv_scatter(desc, pa, sa, n, staging, g.blk_bytes), 7)
+    out["scatter_GBps"] = traffic / ms / 1e6
+    out["batch_blocks"] = n
+    # gather and scatter of disjoint pages and slots on two streams, wall time from a common start
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    walls = []
+    for _ in range(6):
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1, e2 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        s1.wait_event(e0)
+        s2.wait_event(e0)
+        aibx.aibx_kv_gather(desc, pa, sa, n, staging, g.blk_bytes, None, s1)
+        aibx.aibx_kv_scatter(desc, pb, sb, n, staging, g.blk_bytes, None, s2)
+        e1.record(s1)
+        e2.record(s2)
+        torch.cuda.synchronize()
+        walls.append(max(e0.elapsed_time(e1), e0.elapsed_time(e2)))
+    out["two_stream_gather_scatter_GBps"] = 2 * traffic / sorted(walls)[len(walls) // 2] / 1e6
+    del pool, staging
+    torch.cuda.empty_cache()
+    # index + hash at native size
+    B = wl.block_size
+    d_tok = torch.from_numpy(wl.tokens).cuda()
+    d_to, d_bo = torch.from_numpy(wl.tok_off).cuda(), torch.from_numpy(wl.blk_off).cuda()
+    N, R = wl.n_blocks, wl.n_req
+    h = torch.empty(N, dtype=torch.int64, device="cuda")
+    v = torch.empty(N, dtype=torch.int64, device="cuda")
+    m = torch.empty(R, dtype=torch.int32, device="cuda")
+    storage = torch.empty(aibx.aibx_index_storage_bytes(wl.n_slots), dtype=torch.uint8, device="cuda")
+    ix = aibx.aibx_index_create(storage, wl.n_slots)
+    aibx.aibx_block_hash(d_tok, d_to, d_bo, R, N, B, 0, h)
+    vals = torch.arange(N, dtype=torch.int64, device="cuda")
+    c = torch.zeros(5, dtype=torch.int64, device="cuda")
+    aibx.aibx_index_insert(ix, h, vals, N, c[0:3])
+    n_fill = max(0, wl.n_live_target - int(c[0].item()))
+    fk, fv = filler_keys(cfg, max(n_fill, 1))
+    fk, fv = _dev_u64(torch, fk), _dev_u64(torch, fv)
+    if n_fill:
+        aibx.aibx_index_insert(ix, fk, fv, n_fill, c[0:3])
+    ms_h, _ = time_calls(torch, lambda: aibx.aibx_block_hash(d_tok, d_to, d_bo, R, N, B, 0, h), 20)
+    ms_m, _ = time_calls(torch, lambda: aibx.aibx_prefix_match(ix, h, d_bo, R, N, v, m), 20)
+    out["native"] = {"requests": R, "blocks": N, "hash_us": ms_h * 1e3, "match_us": ms_m * 1e3}
+    # update rates: evict then re-insert q filler keys (rounds of the 1:1:4 mix use q = 4096)
+    if n_fill >= 1 << 16:
+        q = 1 << 16
+        ev = torch.empty(q, dtype=torch.int64, device="cuda")
+
+        def churn():
+            aibx.aibx_index_evict(ix, fk[:q], q, ev, c[3:5])
+            aibx.aibx_index_insert(ix, fk[:q], fv[:q], q, c[0:3])
+        ms_c, _ = time_calls(torch, churn, 10)
+        out["evict_plus_insert_Mkeys_per_s"] = 2 * q / ms_c / 1e3
+        q = 4096
+        n_probe = min(N, 4 * q)
+        r_probe = int(np.searchsorted(wl.blk_off, n_probe, side="right")) - 1
+        n_probe = int(wl.blk_off[r_probe])
+
+        def mix_round():
+            aibx.aibx_index_insert(ix, fk[:q], fv[:q], q, c[0:3])
+            aibx.aibx_index_evict(ix, fk[:q], q, ev[:q], c[3:5])
+            aibx.aibx_prefix_match(ix, h, d_bo, r_probe, n_probe, v, m)
+        if r_probe > 0:
+            ms_r, _ = time_calls(torch, mix_round, 20)
+            out["mix_1_1_4_round_us"] = ms_r * 1e3
+            out["mix_1_1_4_Mops_per_s"] = (2 * q + n_probe) / ms_r / 1e3
+    # scaled batch
+    tok, to, bo = make_scaled_tokens(cfg, 4 << 20)
+    Ns, Rs = int(bo[-1]), len(bo) - 1
+    d_tok, d_to, d_bo = torch.from_numpy(tok).cuda(), torch.from_numpy(to).cuda(), torch.from_numpy(bo).cuda()
+    h = torch.empty(Ns, dtype=torch.int64, device="cuda")
+    v = torch.empty(Ns, dtype=torch.int64, device="cuda")
+    m = torch.empty(Rs, dtype=torch.int32, device="cuda")
+    ms_h, _ = time_calls(torch, lambda: aibx.aibx_block_hash(d_tok, d_to, d_bo, Rs, Ns, B, 0, h), 10)
+    ms_m, _ = time_calls(torch, lambda: aibx.aibx_prefix_match(ix, h, d_bo, Rs, Ns, v, m), 10)
+    per = 4 * B + 8 + 8 + 64 + 8
+    rate = Ns / ((ms_h + ms_m) * 1e-3)
+    out["scaled"] = {"requests": Rs, "blocks": Ns, "hash_ms": ms_h, "match_ms": ms_m, "blocks_per_s": rate,
+                     "roofline_frac": rate * per / 1e9 / HBM_PEAK_GBPS, "bytes_per_block": per,
+                     "index_slots": wl.n_slots, "load_factor": wl.load_factor}
+    aibx.aibx_index_destroy(ix)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -249,6 +356,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload (2 = the one the metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-scaled", action="store_true")
+    ap.add_argument("--survey", action="store_true",
+                    help="instead of the headline line, print one JSON line per config (both pool "
+                         "layouts) with copy bandwidths, call latencies and index rates")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain elementwise kernel that reads and writes the staging "
                          "buffer once (known HBM bytes), for scaling profiler counters")
@@ -261,6 +371,11 @@ def main():
     import paper_2504_03648_amd as aibx
     from workloads import make_workload
     torch.cuda.set_device(0)
+    if args.survey:
+        for cfg, layout in [(1, None), (2, None), (2, "page-major"), (3, None), (3, "page-major"), (4, None),
+                            (4, "page-major"), (5, None), (5, "page-major")]:
+            print(json.dumps(survey_config(torch, aibx, cfg, layout)), flush=True)
+        return
     wl = make_workload(args.config, "full")
     step = Step(torch, aibx, wl)
     for _ in range(args.warmup):

@@ -9,9 +9,10 @@
 //  - Loads carry the non-temporal hint; stores to the contiguous staging buffer are written
 //    through at system scope, stores into the paged pool carry the non-temporal hint.
 //  - Tile -> workgroup mapping. Workgroup ids are dealt round-robin over the 8 XCDs, so with the
-//    "XCD-contiguous" map XCD x streams the x-th eighth of the tile sequence; each XCD (own L2,
-//    own translation cache) then works on one contiguous stretch of staging. Gathers from pools
-//    with small segments do slightly better with the plain 2-D map (x = tile in block, y = entry).
+//    "XCD-contiguous" map used here XCD x streams the x-th eighth of the tile sequence: each XCD
+//    (own L2, own translation cache) works on one contiguous stretch of staging and sees whole
+//    segments. Against the plain map (tile = workgroup id) this is worth 2-10 % depending on the
+//    pool geometry, and it never lost in the sweeps.
 #include "common.h"
 
 namespace aibx {
@@ -77,13 +78,6 @@ __device__ __forceinline__ void copy_tile(const CopyArgs& a, const int32_t* __re
   }
 }
 
-// x = tile inside the block, y = entry relative to first_entry
-template <bool kGather, int kThreads>
-__global__ __launch_bounds__(kThreads) void kv_copy_2d_kernel(CopyArgs a, const int32_t* __restrict__ page_ids,
-                                                              const int32_t* __restrict__ slot_ids) {
-  copy_tile<kGather>(a, page_ids, slot_ids, a.first_entry + blockIdx.y, blockIdx.x, kThreads);
-}
-
 // XCD x (= workgroup id mod 8) takes tiles [x*tiles_per_xcd, (x+1)*tiles_per_xcd)
 template <bool kGather, int kThreads>
 __global__ __launch_bounds__(kThreads) void kv_copy_xcd_kernel(CopyArgs a, const int32_t* __restrict__ page_ids,
@@ -109,10 +103,7 @@ int launch_copy(const aibx_pool_desc* pool, const int32_t* d_page_ids, const int
     return AIBX_ERR_ALIGN;
   if (!aligned(d_page_ids, 4) || !aligned(d_slot_ids, 4) || !aligned(d_bad, 8)) return AIBX_ERR_ALIGN;
 
-  // Gathers from small-segment pools: 2-D map, 2 KiB tiles. Everything else: XCD-contiguous
-  // map, 4 KiB tiles.
-  const bool use_2d = kGather && pool->seg_bytes < (128u << 10);
-  const u32 threads = use_2d ? 128 : 256;
+  const u32 threads = 256;  // 4 KiB tiles
   const u64 tile_bytes = (u64)threads * 16;
   const u64 cps = (pool->seg_bytes + tile_bytes - 1) / tile_bytes;
   const u64 tpb = cps * (u64)pool->n_seg;
@@ -133,16 +124,6 @@ int launch_copy(const aibx_pool_desc* pool, const int32_t* d_page_ids, const int
   a.tiles_per_block = (u32)tpb;
   a.total_tiles = a.tiles_per_xcd = 0;
   hipStream_t st = as_stream(stream);
-  if (use_2d) {
-    for (int64_t first = 0; first < n; first += 65535) {  // grid y limit
-      const int64_t n_here = (n - first) < 65535 ? (n - first) : 65535;
-      a.first_entry = first;
-      kv_copy_2d_kernel<kGather, 128><<<dim3((u32)tpb, (u32)n_here), 128, 0, st>>>(a, d_page_ids, d_slot_ids);
-      const int rc = launch_status();
-      if (rc != AIBX_OK) return rc;
-    }
-    return AIBX_OK;
-  }
   // split so that one launch has fewer than 2^31 tiles
   const int64_t max_entries = (int64_t)(0x7FFFFFF0ull / tpb);
   for (int64_t first = 0; first < n; first += max_entries) {
