@@ -9,11 +9,10 @@
 // Invariant kept by every kernel: a probe sequence continues past a bucket only if that bucket
 // has no EMPTY slot; so a lookup stops at the first bucket that has one.
 //
-// Execution shape. Lookups (prefix match): one lane per key, the lane reads the whole bucket.
-// Updates (insert, evict): 8 lanes cooperate on one key - each reads one 16-byte slot, the 8 reads
-// are one coalesced 128-byte line - so that the group can agree on the slot to claim; a wavefront
-// owns 64 consecutive keys, loads them coalesced, and hands key 8g+r to lane group g in step r
-// through cross-lane reads.
+// Execution shape: one lane per key in every kernel; the lane reads its key's whole bucket. Random
+// line reads on this GPU are bound by the number of lines requested (about 55-80 G lines/s whether
+// a line is fetched by one lane or by eight cooperating ones), so lane-per-key costs the memory
+// system nothing extra, needs no cross-lane traffic, and keeps 64 probes per wavefront in flight.
 #include "common.h"
 
 struct aibx_index {
@@ -29,10 +28,7 @@ namespace {
 constexpr u64 kEmpty = AIBX_KEY_EMPTY;
 constexpr u64 kTomb = AIBX_KEY_TOMBSTONE;
 constexpr u64 kNoValue = AIBX_NO_VALUE;
-#ifndef AIBX_BUCKET_SLOTS
-#define AIBX_BUCKET_SLOTS 8
-#endif
-constexpr int kBucket = AIBX_BUCKET_SLOTS;       // slots per bucket = lanes per key (4 or 8)
+constexpr int kBucket = 8;                       // slots per bucket (8 x 16 B = one 128-byte line)
 constexpr u64 kHomeMul = 0x9E3779B97F4A7C15ull;  // multiplicative (Fibonacci) bucket hash
 constexpr int kIndexThreads = 256;
 constexpr int kWavesPerGroup = kIndexThreads / kWave;
@@ -58,15 +54,6 @@ __device__ __forceinline__ u64 shfl64(u64 v, int src) {
   lo = __shfl(lo, src);
   hi = __shfl(hi, src);
   return ((u64)hi << 32) | lo;
-}
-
-// The 8 bits of a wavefront-wide ballot that belong to this lane's group.
-__device__ __forceinline__ u32 group_bits(bool pred, int group) {
-  return (u32)(__ballot(pred) >> (group * kBucket)) & ((1u << kBucket) - 1u);
-}
-
-__device__ __forceinline__ u64 load_key_fresh(const u64* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 typedef __attribute__((ext_vector_type(2))) u64 slot_t;  // .x = key, .y = value
@@ -137,109 +124,133 @@ __global__ __launch_bounds__(kIndexThreads) void prefix_match_kernel(
 }
 
 // ---- insert ------------------------------------------------------------------------------------
-// Counters are summed per wavefront and added once.
+// One lane per key, like the lookups: the lane reads the buckets of its probe sequence, remembers
+// the first free slot, and when the sequence ends without a hit claims that slot with a 64-bit
+// compare-and-swap. Losing the claim to another key means rescanning from that bucket; losing it
+// to the same key (a duplicate in the batch) is an update. Slots only ever go from free to taken
+// while this kernel runs, so two lanes inserting the same key always race for the same slot and
+// the key cannot end up stored twice.
+// The first scan uses ordinary cached loads. Other workgroups are claiming slots at the same time,
+// so that view can be stale - but only towards "free" (a slot it shows taken is taken for good,
+// with the same key), and the compare-and-swap is the arbiter: a claim on a slot that is no longer
+// free fails, and from then on the lane rescans with agent-scope loads. This keeps the common paths
+// (update of a present key, claim of a free slot) at one line read plus one write.
+__device__ __forceinline__ u64 load_key_fresh(const u64* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Values are written with ordinary stores: nothing reads a value before the kernel ends (lookups
+// and evictions run in later launches), and the bytes of a value are written by one key's lanes
+// only (duplicates of a key in a batch carry the same value).
+__device__ __forceinline__ void store_value(u64* p, u64 v) { *p = v; }
+
+__device__ __forceinline__ u32 wave_sum(u32 v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m);
+  return v;
+}
+
+// Sum over the workgroup (every thread must call it); valid in thread 0. Counters are added with
+// one atomic per workgroup and the grids are capped, because atomics on one address serialise at
+// about 13 ns each: one per wavefront made a 12 M-key insert spend 2.3 ms on its counters alone.
+__device__ __forceinline__ u32 group_sum(u32 v) {
+  __shared__ u32 part[kWavesPerGroup];
+  v = wave_sum(v);
+  __syncthreads();  // a previous call's readers are done with part[]
+  if ((threadIdx.x & (kWave - 1)) == 0) part[threadIdx.x / kWave] = v;
+  __syncthreads();
+  u32 total = 0;
+  if (threadIdx.x == 0)
+    for (int w = 0; w < kWavesPerGroup; ++w) total += part[w];
+  return total;
+}
+
 __global__ __launch_bounds__(kIndexThreads) void index_insert_kernel(
     Table t, const u64* __restrict__ keys, const u64* __restrict__ values, int64_t n,
     u64* __restrict__ counters3) {
-  const int lane = threadIdx.x & (kWave - 1);
-  const int group = lane / kBucket, sub = lane % kBucket;
-  const int64_t base = ((int64_t)blockIdx.x * kWavesPerGroup + threadIdx.x / kWave) * kWave;
-  if (base >= n) return;
-  const int64_t left = n - base;
-  const int n_valid = left < kWave ? (int)left : kWave;
-  const u64 my_key = lane < n_valid ? keys[base + lane] : kEmpty;
-  const u64 my_val = lane < n_valid ? values[base + lane] : 0ull;
-  u32 n_ins = 0, n_upd = 0, n_full = 0;  // meaningful in lanes with sub == 0
+  u32 n_ins = 0, n_upd = 0, n_full = 0;
   const u64 n_buckets = t.bucket_mask + 1;
-
-  for (int r = 0; r < kBucket; ++r) {
-    const u64 key = shfl64(my_key, group * kBucket + r);
-    const u64 val = shfl64(my_val, group * kBucket + r);
-    const bool real = group * kBucket + r < n_valid;
-    bool active = real && key != kEmpty && key != kTomb;
-    if (real && !active) ++n_full;  // reserved key: dropped
-    u64 b = home_bucket(t, key);
-    const u64 step = probe_step(key);
-    u64 probes = 0;                 // buckets fully scanned so far
-    // candidate free slot (first in probe order); kept by the lane that owns it
-    bool have_cand = false;         // group-uniform
-    u64 cand_bucket = 0, cand_probes = 0;
-    int cand_sub = 0;               // group-uniform
-    u64 cand_expected = 0;          // valid in lane cand_sub
-    // Proven bound on loop trips: a scan visits at most n_buckets buckets, and a scan is repeated
-    // only after a lost claim, i.e. after some other insert filled a slot (at most n_slots times).
-    u64 guard = n_buckets > (1ull << 30) ? ~0ull : n_buckets * (n_buckets * kBucket + 1);
-    while (__any(active)) {
-      u64* slot = t.slots + 2 * (b * kBucket + sub);
-      const u64 seen = active ? load_key_fresh(slot) : kEmpty;
-      const u32 hit = group_bits(active && seen == key, group);
-      const u32 free_ = group_bits(active && (seen == kEmpty || seen == kTomb), group);
-      const u32 empty = group_bits(active && seen == kEmpty, group);
-      // the probe sequence ends at a bucket with an EMPTY slot, or after every bucket was seen
-      const bool chain_ends = empty != 0 || probes + 1 >= n_buckets;
-      bool claim = false;
-      if (active) {
-        if (hit) {  // present: overwrite the value
-          if (sub == __ffs(hit) - 1) __hip_atomic_store(slot + 1, val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          ++n_upd;
-          active = false;
-        } else {
-          if (!have_cand && free_) {
-            have_cand = true;
-            cand_sub = __ffs(free_) - 1;
-            cand_bucket = b;
-            cand_probes = probes;
-            if (sub == cand_sub) cand_expected = seen;
-          }
-          if (!chain_ends) {
-            b = (b + step) & t.bucket_mask;
-            ++probes;
-          } else if (!have_cand) {
-            ++n_full;  // every slot of the table is taken
-            active = false;
-          } else {
-            claim = true;  // key is absent: take the first free slot of its probe sequence
-          }
-        }
+  for (int64_t i = (int64_t)blockIdx.x * kIndexThreads + threadIdx.x; i < n; i += (int64_t)gridDim.x * kIndexThreads) {
+  const u64 key = keys[i];
+  const u64 val = values[i];
+  bool active = key != kEmpty && key != kTomb;
+  if (!active) ++n_full;  // reserved key: dropped
+  const u64 step = probe_step(key);
+  u64 b = home_bucket(t, key);
+  u64 probes = 0;  // buckets of the probe sequence already examined
+  bool have_cand = false;
+  u64 cand_bucket = 0, cand_probes = 0, cand_expected = 0;
+  int cand_slot = 0;
+  // Proven bound on loop trips: a scan visits at most n_buckets buckets, and a scan is repeated
+  // only after a lost claim, i.e. after some other insert filled a slot (at most n_slots times).
+  u64 guard = n_buckets > (1ull << 30) ? ~0ull : n_buckets * (n_buckets * kBucket + 1);
+  bool fresh = false;  // set after a lost claim
+  while (active) {
+    u64* bucket = t.slots + 2 * b * kBucket;
+    u64 seen[kBucket];
+    if (fresh) {
+#pragma unroll
+      for (int j = 0; j < kBucket; ++j) seen[j] = load_key_fresh(bucket + 2 * j);
+    } else {
+#pragma unroll
+      for (int j = 0; j < kBucket; ++j) seen[j] = reinterpret_cast<const slot_t*>(bucket)[j].x;
+    }
+    int hit = -1, first_free = -1;
+    bool any_empty = false;
+#pragma unroll
+    for (int j = kBucket - 1; j >= 0; --j) {
+      if (seen[j] == key) hit = j;
+      if (seen[j] == kEmpty || seen[j] == kTomb) first_free = j;
+      any_empty |= seen[j] == kEmpty;
+    }
+    if (hit >= 0) {  // present: overwrite the value
+      store_value(bucket + 2 * hit + 1, val);
+      ++n_upd;
+      break;
+    }
+    if (!have_cand && first_free >= 0) {
+      have_cand = true;
+      cand_bucket = b;
+      cand_probes = probes;
+      cand_slot = first_free;
+      cand_expected = seen[0];
+#pragma unroll
+      for (int j = 1; j < kBucket; ++j) cand_expected = first_free == j ? seen[j] : cand_expected;
+    }
+    // the probe sequence ends at a bucket with an EMPTY slot, or after every bucket was seen
+    if (!any_empty && probes + 1 < n_buckets) {
+      b = (b + step) & t.bucket_mask;
+      ++probes;
+    } else if (!have_cand) {
+      ++n_full;  // every slot of the table is taken
+      break;
+    } else {
+      u64* cslot = t.slots + 2 * (cand_bucket * kBucket + cand_slot);
+      const u64 old = atomicCAS((unsigned long long*)cslot, (unsigned long long)cand_expected,
+                                (unsigned long long)key);
+      if (old == cand_expected) {  // the slot is ours
+        store_value(cslot + 1, val);
+        ++n_ins;
+        break;
       }
-      // claim step (all lanes take part in the cross-lane reads)
-      u64* cslot = t.slots + 2 * (cand_bucket * kBucket + sub);
-      u64 old = 0;
-      if (claim && sub == cand_sub)
-        old = atomicCAS((unsigned long long*)cslot, (unsigned long long)cand_expected, (unsigned long long)key);
-      const u64 old_g = shfl64(old, group * kBucket + cand_sub);
-      const u64 exp_g = shfl64(cand_expected, group * kBucket + cand_sub);
-      if (claim) {
-        if (old_g == exp_g) {          // slot is ours
-          if (sub == cand_sub) __hip_atomic_store(cslot + 1, val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          ++n_ins;
-          active = false;
-        } else if (old_g == key) {     // the same key was stored there a moment ago
-          if (sub == cand_sub) __hip_atomic_store(cslot + 1, val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          ++n_upd;
-          active = false;
-        } else {                       // another key took it: rescan from that bucket
-          b = cand_bucket;
-          probes = cand_probes;
-          have_cand = false;
-        }
+      if (old == key) {  // the same key was stored there a moment ago
+        store_value(cslot + 1, val);
+        ++n_upd;
+        break;
       }
-      if (--guard == 0 && active) {
-        ++n_full;
-        active = false;
-      }
+      b = cand_bucket;  // another key took it: rescan from that bucket, with fresh loads
+      probes = cand_probes;
+      have_cand = false;
+      fresh = true;
+    }
+    if (--guard == 0) {
+      ++n_full;
+      break;
     }
   }
+  }  // keys of this lane
   if (counters3) {
-    const bool leader = sub == 0;
-    u32 a = leader ? n_ins : 0, u = leader ? n_upd : 0, f = leader ? n_full : 0;
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) {
-      a += __shfl_xor(a, m);
-      u += __shfl_xor(u, m);
-      f += __shfl_xor(f, m);
-    }
-    if (lane == 0) {
+    const u32 a = group_sum(n_ins), u = group_sum(n_upd), f = group_sum(n_full);
+    if (threadIdx.x == 0) {
       if (a) atomicAdd((unsigned long long*)counters3 + 0, (unsigned long long)a);
       if (u) atomicAdd((unsigned long long*)counters3 + 1, (unsigned long long)u);
       if (f) atomicAdd((unsigned long long*)counters3 + 2, (unsigned long long)f);
@@ -248,73 +259,55 @@ __global__ __launch_bounds__(kIndexThreads) void index_insert_kernel(
 }
 
 // ---- evict -------------------------------------------------------------------------------------
+// One lane per key. The key's slot goes back to EMPTY when its bucket still has an EMPTY slot
+// (such a bucket ends every probe sequence that reaches it, so nothing lies beyond it), otherwise
+// it becomes a tombstone. The compare-and-swap decides which of several entries naming the same
+// key reports the value. Ordinary cached loads suffice: while this kernel runs slots only go from
+// taken to free, so a stale view can only show a key that is already gone (the swap then fails and
+// the entry counts as missing) or overlook a fresh EMPTY (a tombstone is written where EMPTY
+// would have done, or the scan goes one bucket further than needed).
 __global__ __launch_bounds__(kIndexThreads) void index_evict_kernel(
     Table t, const u64* __restrict__ keys, int64_t n, u64* __restrict__ values_out,
     u64* __restrict__ counters2) {
-  const int lane = threadIdx.x & (kWave - 1);
-  const int group = lane / kBucket, sub = lane % kBucket;
-  const int64_t base = ((int64_t)blockIdx.x * kWavesPerGroup + threadIdx.x / kWave) * kWave;
-  if (base >= n) return;
-  const int64_t left = n - base;
-  const int n_valid = left < kWave ? (int)left : kWave;
-  const u64 my_key = lane < n_valid ? keys[base + lane] : kEmpty;
-  u64 my_out = kNoValue;
   u32 n_ev = 0, n_miss = 0;
   const u64 n_buckets = t.bucket_mask + 1;
-
-  for (int r = 0; r < kBucket; ++r) {
-    const u64 key = shfl64(my_key, group * kBucket + r);
-    const bool real = group * kBucket + r < n_valid;
-    bool active = real && key != kEmpty && key != kTomb;
-    if (real && !active) ++n_miss;
-    u64 b = home_bucket(t, key);
-    const u64 step = probe_step(key);
-    u64 probes = 0;
-    u64 result = kNoValue;  // group-uniform
-    while (__any(active)) {
-      u64* slot = t.slots + 2 * (b * kBucket + sub);
-      const u64 seen = active ? load_key_fresh(slot) : kEmpty;
-      const u32 hit = group_bits(active && seen == key, group);
-      const u32 empty = group_bits(active && seen == kEmpty, group);
-      u64 old = 0, val = 0;
-      const int hit_sub = hit ? __ffs(hit) - 1 : 0;
-      if (active && hit && sub == hit_sub) {
-        // a bucket that still has an EMPTY slot ends every probe sequence through it, so its
-        // removed slots can go straight back to EMPTY; otherwise leave a tombstone
-        old = atomicCAS((unsigned long long*)slot, (unsigned long long)key,
-                        (unsigned long long)(empty ? kEmpty : kTomb));
-        if (old == key) val = slot[1];
-      }
-      const u64 old_g = shfl64(old, group * kBucket + hit_sub);
-      const u64 val_g = shfl64(val, group * kBucket + hit_sub);
-      if (active) {
-        if (hit) {
-          if (old_g == key) { result = val_g; ++n_ev; }
-          else ++n_miss;              // another entry of this batch removed it first
-          active = false;
-        } else if (empty || probes + 1 >= n_buckets) {
-          ++n_miss;
-          active = false;
-        } else {
-          b = (b + step) & t.bucket_mask;
-          ++probes;
-        }
-      }
-    }
-    if (sub == r) my_out = result;
-  }
-  if (values_out && lane < n_valid) values_out[base + lane] = my_out;
-  if (counters2) {
-    const bool leader = sub == 0;
-    u32 e = leader ? n_ev : 0, m2 = leader ? n_miss : 0;
+  for (int64_t i = (int64_t)blockIdx.x * kIndexThreads + threadIdx.x; i < n; i += (int64_t)gridDim.x * kIndexThreads) {
+  const u64 key = keys[i];
+  u64 result = kNoValue;
+  bool active = key != kEmpty && key != kTomb;
+  const u64 step = probe_step(key);
+  u64 b = home_bucket(t, key);
+  for (u64 probes = 0; active; ++probes) {
+    u64* bucket = t.slots + 2 * b * kBucket;
+    u64 seen[kBucket];
 #pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) {
-      e += __shfl_xor(e, m);
-      m2 += __shfl_xor(m2, m);
+    for (int j = 0; j < kBucket; ++j) seen[j] = reinterpret_cast<const slot_t*>(bucket)[j].x;
+    int hit = -1;
+    bool any_empty = false;
+#pragma unroll
+    for (int j = 0; j < kBucket; ++j) {
+      if (seen[j] == key) hit = j;
+      any_empty |= seen[j] == kEmpty;
     }
-    if (lane == 0) {
+    if (hit >= 0) {
+      u64* slot = bucket + 2 * hit;
+      const u64 old = atomicCAS((unsigned long long*)slot, (unsigned long long)key,
+                                (unsigned long long)(any_empty ? kEmpty : kTomb));
+      if (old == key) result = slot[1];  // otherwise another entry of this batch removed it first
+      break;
+    }
+    if (any_empty || probes + 1 >= n_buckets) break;
+    b = (b + step) & t.bucket_mask;
+  }
+  if (values_out) values_out[i] = result;
+  if (result != kNoValue) ++n_ev;
+  else ++n_miss;
+  }  // keys of this lane
+  if (counters2) {
+    const u32 e = group_sum(n_ev), m = group_sum(n_miss);
+    if (threadIdx.x == 0) {
       if (e) atomicAdd((unsigned long long*)counters2 + 0, (unsigned long long)e);
-      if (m2) atomicAdd((unsigned long long*)counters2 + 1, (unsigned long long)m2);
+      if (m) atomicAdd((unsigned long long*)counters2 + 1, (unsigned long long)m);
     }
   }
 }
@@ -381,7 +374,7 @@ int check_slots(u64 n_slots) {
 
 u32 pass_grid(u64 n_items) {
   const u64 want = (n_items + kIndexThreads - 1) / kIndexThreads;
-  return (u32)(want < 1 ? 1 : (want > 8192 ? 8192 : want));
+  return (u32)(want < 1 ? 1 : (want > 2048 ? 2048 : want));  // 2048 x 256 lanes fill the GPU once
 }
 
 }  // namespace
@@ -441,10 +434,8 @@ int aibx_index_insert(aibx_index_t* index, const uint64_t* d_keys, const uint64_
   if (n == 0) return AIBX_OK;
   if (!d_keys || !d_values) return AIBX_ERR_INVALID_ARG;
   if (!aligned(d_keys, 8) || !aligned(d_values, 8) || !aligned(d_counters3, 8)) return AIBX_ERR_ALIGN;
-  const int64_t groups = (n + kIndexThreads - 1) / kIndexThreads;
-  if (groups > 0x7FFFFFFF) return AIBX_ERR_UNSUPPORTED;
-  index_insert_kernel<<<(u32)groups, kIndexThreads, 0, as_stream(stream)>>>(table_of(index), d_keys, d_values, n,
-                                                                            d_counters3);
+  index_insert_kernel<<<pass_grid((u64)n), kIndexThreads, 0, as_stream(stream)>>>(table_of(index), d_keys, d_values,
+                                                                                   n, d_counters3);
   return launch_status();
 }
 
@@ -454,10 +445,8 @@ int aibx_index_evict(aibx_index_t* index, const uint64_t* d_keys, int64_t n, uin
   if (n == 0) return AIBX_OK;
   if (!d_keys) return AIBX_ERR_INVALID_ARG;
   if (!aligned(d_keys, 8) || !aligned(d_values_out, 8) || !aligned(d_counters2, 8)) return AIBX_ERR_ALIGN;
-  const int64_t groups = (n + kIndexThreads - 1) / kIndexThreads;
-  if (groups > 0x7FFFFFFF) return AIBX_ERR_UNSUPPORTED;
-  index_evict_kernel<<<(u32)groups, kIndexThreads, 0, as_stream(stream)>>>(table_of(index), d_keys, n,
-                                                                           d_values_out, d_counters2);
+  index_evict_kernel<<<pass_grid((u64)n), kIndexThreads, 0, as_stream(stream)>>>(table_of(index), d_keys, n,
+                                                                                  d_values_out, d_counters2);
   return launch_status();
 }
 
