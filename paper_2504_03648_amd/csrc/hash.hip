@@ -5,9 +5,10 @@
 // Layout of the work: one workgroup of 4 wavefronts (or, for large batches, 1) per request. A wavefront takes a
 // tile of 1024 consecutive tokens (64 coalesced tokens per load, 16 loads in flight), so a lane
 // always sees the same position-in-block and folds its position constant once. The per-block sums
-// are formed by a transposing butterfly across the lanes that share a block, the block digests
-// are scanned across lanes with the chain's affine step (s -> K2*s + d), and the carry between
-// tiles of one request goes through LDS.
+// are formed by a transposing butterfly across the lanes that share a block (DPP lane patterns
+// inside a row of 16 lanes, bpermute only across rows), the block digests are scanned with the
+// chain's affine step (s -> K2*s + d) by DPP row shifts inside each row and a 4-step scalar chain
+// across rows, and the carry between tiles of one request goes through LDS.
 #include "common.h"
 
 namespace aibx {
@@ -68,7 +69,7 @@ __device__ __forceinline__ u64 shfl_up64(u64 v, int d) {
 }
 
 // Inclusive scan of the affine chain over lanes 0..kN-1: on return lane l holds
-// sum_{k<=l} K2^(l-k) * d_k.
+// sum_{k<=l} K2^(l-k) * d_k. (General path.)
 template <int kN>
 __device__ __forceinline__ u64 chain_scan(u64 d, int lane) {
 #pragma unroll
@@ -77,6 +78,35 @@ __device__ __forceinline__ u64 chain_scan(u64 d, int lane) {
     if (lane >= o) d += ipow(K2, o) * up;
   }
   return d;
+}
+
+// 64-bit value through a DPP lane pattern (a VALU operand modifier: no LDS round trip). Lanes
+// whose source is outside the row read 0.
+template <int kCtrl>
+__device__ __forceinline__ u64 dpp64(u64 v) {
+  const u32 lo = (u32)__builtin_amdgcn_update_dpp(0, (int)(u32)v, kCtrl, 0xF, 0xF, true);
+  const u32 hi = (u32)__builtin_amdgcn_update_dpp(0, (int)(u32)(v >> 32), kCtrl, 0xF, 0xF, true);
+  return ((u64)hi << 32) | lo;
+}
+constexpr int kDppRowMirror = 0x140, kDppRowHalfMirror = 0x141, kDppQuadReverse = 0x1B, kDppQuadSwap = 0xB1;
+constexpr int kDppRowShr = 0x110;  // + shift (1..15)
+
+// Value of the butterfly partner across lane bit kMask. Any partner on the other side of that bit
+// will do as long as later levels stay inside the halves this level made, so inside a row of 16
+// lanes the mirror patterns serve (15-i, 7-i, 3-i, i^1); across rows it takes a bpermute.
+template <int kMask>
+__device__ __forceinline__ u64 partner64(u64 v) {
+  if constexpr (kMask >= 16) return shfl_xor64(v, kMask);
+  else if constexpr (kMask == 8) return dpp64<kDppRowMirror>(v);
+  else if constexpr (kMask == 4) return dpp64<kDppRowHalfMirror>(v);
+  else if constexpr (kMask == 2) return dpp64<kDppQuadReverse>(v);
+  else return dpp64<kDppQuadSwap>(v);
+}
+
+__device__ __forceinline__ u64 readlane64(u64 v, int lane) {
+  const u32 lo = (u32)__builtin_amdgcn_readlane((int)(u32)v, lane);
+  const u32 hi = (u32)__builtin_amdgcn_readlane((int)(u32)(v >> 32), lane);
+  return ((u64)hi << 32) | lo;
 }
 
 // ---- fast path: block sizes 16, 32, 64 -------------------------------------------------------
@@ -102,12 +132,14 @@ __global__ __launch_bounds__(kHashWaves* kWave) void block_hash_pow2_kernel(
   u64* out = hash_out + b0;
 
   const u64 pos_const = K0 * (u64)((lane & (kB - 1)) + 1);
-  // K2^(lane+1): weight of the carry-in at this lane's block
-  u64 carry_w = 1;
+  // K2^(pos+1), pos = lane within its row of 16: weight of the state entering the row
+  constexpr int kRows = kNB >= 16 ? kNB / 16 : 1;
+  const int row = lane >> 4;
+  u64 row_w = 1;
   {
     u64 sq = K2;
-    for (int bit = 0; bit < 7; ++bit) {
-      if ((lane + 1) >> bit & 1) carry_w *= sq;
+    for (int bit = 0; bit < 5; ++bit) {
+      if (((lane & 15) + 1) >> bit & 1) row_w *= sq;
       sq *= sq;
     }
   }
@@ -123,10 +155,15 @@ __global__ __launch_bounds__(kHashWaves* kWave) void block_hash_pow2_kernel(
     u64 p[kLoads];
     // 16 coalesced loads; tokens past the last full block read as 0 and are never used
     int32_t raw[kLoads];
+    if (tbase + kTileTokens <= n_tok) {  // whole tile inside the request: no per-load bounds checks
 #pragma unroll
-    for (int k = 0; k < kLoads; ++k) {
-      const int64_t idx = tbase + k * kWave + lane;
-      raw[k] = (tile < n_tiles && idx < n_tok) ? __builtin_nontemporal_load(tok + idx) : 0;
+      for (int k = 0; k < kLoads; ++k) raw[k] = __builtin_nontemporal_load(tok + tbase + k * kWave + lane);
+    } else {
+#pragma unroll
+      for (int k = 0; k < kLoads; ++k) {
+        const int64_t idx = tbase + k * kWave + lane;
+        raw[k] = (tile < n_tiles && idx < n_tok) ? __builtin_nontemporal_load(tok + idx) : 0;
+      }
     }
 #pragma unroll
     for (int k = 0; k < kLoads; ++k) {
@@ -141,7 +178,7 @@ __global__ __launch_bounds__(kHashWaves* kWave) void block_hash_pow2_kernel(
       for (int t = 0; t < 8; ++t) {
         const u64 send = up ? p[t] : p[t + 8];
         const u64 keep = up ? p[t + 8] : p[t];
-        q8[t] = keep + shfl_xor64(send, kB / 2);
+        q8[t] = keep + partner64<kB / 2>(send);
       }
     }
     {
@@ -150,7 +187,7 @@ __global__ __launch_bounds__(kHashWaves* kWave) void block_hash_pow2_kernel(
       for (int t = 0; t < 4; ++t) {
         const u64 send = up ? q8[t] : q8[t + 4];
         const u64 keep = up ? q8[t + 4] : q8[t];
-        q4[t] = keep + shfl_xor64(send, kB / 4);
+        q4[t] = keep + partner64<kB / 4>(send);
       }
     }
     {
@@ -159,39 +196,55 @@ __global__ __launch_bounds__(kHashWaves* kWave) void block_hash_pow2_kernel(
       for (int t = 0; t < 2; ++t) {
         const u64 send = up ? q4[t] : q4[t + 2];
         const u64 keep = up ? q4[t + 2] : q4[t];
-        q2[t] = keep + shfl_xor64(send, kB / 8);
+        q2[t] = keep + partner64<kB / 8>(send);
       }
     }
     {
       const bool up = lane & (kB / 16);
       const u64 send = up ? q2[0] : q2[1];
       const u64 keep = up ? q2[1] : q2[0];
-      c = keep + shfl_xor64(send, kB / 16);
+      c = keep + partner64<kB / 16>(send);
     }
-#pragma unroll
-    for (int m = kB / 32; m >= 1; m >>= 1) c += shfl_xor64(c, m);
+    if constexpr (kB >= 64) c += partner64<2>(c);
+    if constexpr (kB >= 32) c += partner64<1>(c);
     // now the lane with load index k = (lane >> (kLgB-4)) & 15 and group g = lane / kB holds the
     // sum of block k*kGroups + g; bring block `lane` to lane `lane`
     c = shfl64(c, src_lane);
     const int64_t jb = tile * kNB + lane;  // block index inside the request
     const bool valid = lane < kNB && jb < n_r;
-    u64 d = valid ? fin(c) : 0ull;
-    const u64 local = chain_scan<kNB>(d, lane);
-    // tile aggregate = scan value at the tile's last block (earlier tiles are always full)
-    const u64 aggr = shfl64(local, kNB - 1);
-    if (kHashWaves == 1) {  // one wavefront per request: the carry stays in registers
-      if (valid) out[jb] = out_hash(carry_w * carry + local);
-      carry = ipow(K2, kNB) * carry + aggr;
-      continue;
+    u64 local = valid ? fin(c) : 0ull;
+    // chain, level 1: scan inside each row of 16 lanes (DPP row shifts feed 0 into the row's
+    // first lanes, so no lane needs a condition)
+    local += ipow(K2, 1) * dpp64<kDppRowShr + 1>(local);
+    local += ipow(K2, 2) * dpp64<kDppRowShr + 2>(local);
+    local += ipow(K2, 4) * dpp64<kDppRowShr + 4>(local);
+    local += ipow(K2, 8) * dpp64<kDppRowShr + 8>(local);
+    // chain, level 2: the state entering each row. y[r] = state entering row r if the tile started
+    // from 0; the tile's aggregate is the state leaving its last row.
+    u64 y[kRows + 1];
+    y[0] = 0;
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) y[r + 1] = ipow(K2, 16) * y[r] + readlane64(local, 16 * r + 15);
+    const u64 aggr = y[kRows];
+    u64 cin = carry;  // chain state entering this wavefront's tile
+    if constexpr (kHashWaves > 1) {
+      if (lane == 0) lds_aggr[parity][wave] = aggr;
+      __syncthreads();
+      for (int w = 0; w < wave; ++w) cin = ipow(K2, kNB) * cin + lds_aggr[parity][w];
     }
-    if (lane == 0) lds_aggr[parity][wave] = aggr;
-    __syncthreads();
-    u64 cin = carry;
-    for (int w = 0; w < wave; ++w) cin = ipow(K2, kNB) * cin + lds_aggr[parity][w];
-    if (valid) out[jb] = out_hash(carry_w * cin + local);
-    // chain state after all tiles of this iteration (only used if another iteration follows,
-    // in which case every tile of this one was full)
-    for (int w = 0; w < kHashWaves; ++w) carry = ipow(K2, kNB) * carry + lds_aggr[parity][w];
+    // state entering this lane's row = y[row] + K2^(16*row) * cin; this lane's block then adds
+    // K2^(pos+1) times that to its in-row scan value
+    u64 enter = cin;
+#pragma unroll
+    for (int r = 1; r < kRows; ++r) enter = row == r ? y[r] + ipow(K2, 16 * r) * cin : enter;
+    if (valid) out[jb] = out_hash(row_w * enter + local);
+    if constexpr (kHashWaves > 1) {
+      // chain state after all tiles of this iteration (only used if another iteration follows,
+      // in which case every tile of this one was full)
+      for (int w = 0; w < kHashWaves; ++w) carry = ipow(K2, kNB) * carry + lds_aggr[parity][w];
+    } else {
+      carry = ipow(K2, kNB) * carry + aggr;
+    }
   }
 }
 
