@@ -190,10 +190,14 @@ def scaled_hash_match(torch, aibx, cfg, step, min_blocks):
     B = step.wl.block_size
     hash_ms, _ = time_calls(torch, lambda: aibx.aibx_block_hash(d_tok, d_to, d_bo, R, N, B, 0, h), 10)
     match_ms, _ = time_calls(torch, lambda: aibx.aibx_prefix_match(step.ix, h, d_bo, R, N, v, m), 10)
+    fused_ms, _ = time_calls(torch, lambda: aibx.aibx_hash_match(step.ix, d_tok, d_to, d_bo, R, N, B, 0, h, v, m), 10)
     per_block = 4 * B + 8 + 8 + 64 + 8
     t = (hash_ms + match_ms) * 1e-3
     rate = N / t
+    fused_rate = N / (fused_ms * 1e-3)
     return {
+        "fused_one_launch": {"ms": fused_ms, "blocks_per_s": fused_rate,
+                             "roofline_frac": fused_rate * per_block / 1e9 / HBM_PEAK_GBPS},
         "workload": f"config {cfg} request mix replicated to {R} requests / {N} blocks / {len(tok)} tokens",
         "blocks_per_s": rate, "hash_ms": hash_ms, "match_ms": match_ms,
         "hash_GBps": N * (4 * B + 8) / (hash_ms * 1e-3) / 1e9,

@@ -8,6 +8,7 @@
  *
  *   aibx_block_hash    chained per-block hashes of request token streams
  *   aibx_prefix_match  lookup of those hashes in a GPU-resident cache index + first-miss length
+ *   aibx_hash_match    the two above in one launch
  *   aibx_index_insert  metadata update: (key -> value) upsert           (Section 3.2.5)
  *   aibx_index_evict   metadata update: removal of evicted keys          (Section 3.2.5)
  *   aibx_kv_gather     paged KV pool -> contiguous staging (offload)     (Section 3.2.5)
@@ -157,6 +158,19 @@ int aibx_index_dump(const aibx_index_t* index, uint64_t* d_keys_out, uint64_t* d
 int aibx_prefix_match(const aibx_index_t* index, const uint64_t* d_hashes,
                       const int64_t* d_blk_off, int32_t n_req, int64_t n_blocks_total,
                       uint64_t* d_values_out, int32_t* d_match_len, void* stream);
+
+/* Hash and match in one launch: the same results as aibx_block_hash followed by
+ * aibx_prefix_match on its output (Section 3.2.2: the routing path hashes a request's tokens only
+ * to look the blocks up), without the hashes travelling through memory between two launches.
+ *   d_hash_out   uint64[n_blocks_total], nullable (required when block_size is not 16, 32 or 64:
+ *                those sizes run as the two separate launches);
+ *   d_values_out uint64[n_blocks_total], nullable; d_match_len int32[n_req];
+ *   every other argument as in aibx_block_hash / aibx_prefix_match.
+ * Errors: INVALID_ARG, ALIGN, UNSUPPORTED (block size outside {16,32,64} with d_hash_out NULL), HIP. */
+int aibx_hash_match(const aibx_index_t* index, const int32_t* d_tokens, const int64_t* d_tok_off,
+                    const int64_t* d_blk_off, int32_t n_req, int64_t n_blocks_total,
+                    int32_t block_size, uint64_t seed, uint64_t* d_hash_out,
+                    uint64_t* d_values_out, int32_t* d_match_len, void* stream);
 
 /* ------------------------------------------------------------------------------------------
  * Paged-KV gather / scatter.  (Moving KV blocks between the engine's paged memory and the

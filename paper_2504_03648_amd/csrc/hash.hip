@@ -9,7 +9,7 @@
 // inside a row of 16 lanes, bpermute only across rows), the block digests are scanned with the
 // chain's affine step (s -> K2*s + d) by DPP row shifts inside each row and a 4-step scalar chain
 // across rows, and the carry between tiles of one request goes through LDS.
-#include "common.h"
+#include "index_device.h"
 
 namespace aibx {
 namespace {
@@ -51,13 +51,6 @@ __device__ __forceinline__ u64 shfl_xor64(u64 v, int mask) {
   u32 lo = (u32)v, hi = (u32)(v >> 32);
   lo = __shfl_xor(lo, mask);
   hi = __shfl_xor(hi, mask);
-  return ((u64)hi << 32) | lo;
-}
-
-__device__ __forceinline__ u64 shfl64(u64 v, int src) {
-  u32 lo = (u32)v, hi = (u32)(v >> 32);
-  lo = __shfl(lo, src);
-  hi = __shfl(hi, src);
   return ((u64)hi << 32) | lo;
 }
 
@@ -110,15 +103,26 @@ __device__ __forceinline__ u64 readlane64(u64 v, int lane) {
 }
 
 // ---- fast path: block sizes 16, 32, 64 -------------------------------------------------------
-template <int kB, int kHashWaves>
+// With kMatch the kernel also looks every hash up in the index as soon as it is formed (one lane
+// per block, the lane reads the whole bucket) and reduces the first miss of the request, so the
+// probe latency of one wavefront overlaps the hash arithmetic of the others and the hashes need not
+// travel through memory between two launches.
+struct MatchOut {
+  Table table;
+  u64* values_out;      // nullable
+  int32_t* match_len;
+};
+
+template <int kB, int kHashWaves, bool kMatch>
 __global__ __launch_bounds__(kHashWaves* kWave) void block_hash_pow2_kernel(
     const int32_t* __restrict__ tokens, const int64_t* __restrict__ tok_off,
-    const int64_t* __restrict__ blk_off, u64 seed, u64* __restrict__ hash_out) {
+    const int64_t* __restrict__ blk_off, u64 seed, u64* __restrict__ hash_out, MatchOut mo) {
   static_assert(kB == 16 || kB == 32 || kB == 64, "block size");
   constexpr int kNB = kTileTokens / kB;   // blocks per tile
   constexpr int kGroups = kWave / kB;     // blocks covered by one 64-token load
   constexpr int kLgB = kB == 16 ? 4 : (kB == 32 ? 5 : 6);
   __shared__ u64 lds_aggr[2][kHashWaves];
+  __shared__ int lds_first[kHashWaves];
 
   const int r = blockIdx.x;
   const int lane = threadIdx.x & (kWave - 1);
@@ -126,7 +130,11 @@ __global__ __launch_bounds__(kHashWaves* kWave) void block_hash_pow2_kernel(
   const int64_t t0 = tok_off[r];
   const int64_t b0 = blk_off[r];
   const int64_t n_r = blk_off[r + 1] - b0;
-  if (n_r <= 0) return;
+  if (n_r <= 0) {
+    if (kMatch && threadIdx.x == 0) mo.match_len[r] = 0;
+    return;
+  }
+  int64_t first_miss = n_r;
   const int64_t n_tok = n_r * kB;  // tokens that belong to full blocks
   const int32_t* tok = tokens + t0;
   u64* out = hash_out + b0;
@@ -237,13 +245,33 @@ __global__ __launch_bounds__(kHashWaves* kWave) void block_hash_pow2_kernel(
     u64 enter = cin;
 #pragma unroll
     for (int r = 1; r < kRows; ++r) enter = row == r ? y[r] + ipow(K2, 16 * r) * cin : enter;
-    if (valid) out[jb] = out_hash(row_w * enter + local);
+    const u64 h = out_hash(row_w * enter + local);
+    if (valid && (!kMatch || hash_out)) out[jb] = h;
+    if constexpr (kMatch) {
+      const u64 v = lookup_one(mo.table, h, valid);
+      if (valid && mo.values_out) mo.values_out[b0 + jb] = v;
+      const u64 miss = __ballot(valid && v == kNoValue);
+      if (miss && first_miss == n_r) first_miss = tile * kNB + (__ffsll((unsigned long long)miss) - 1);
+    }
     if constexpr (kHashWaves > 1) {
       // chain state after all tiles of this iteration (only used if another iteration follows,
       // in which case every tile of this one was full)
       for (int w = 0; w < kHashWaves; ++w) carry = ipow(K2, kNB) * carry + lds_aggr[parity][w];
     } else {
       carry = ipow(K2, kNB) * carry + aggr;
+    }
+  }
+  if constexpr (kMatch) {
+    if (kHashWaves == 1) {
+      if (lane == 0) mo.match_len[r] = (int)first_miss;
+    } else {
+      if (lane == 0) lds_first[wave] = (int)first_miss;
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        int m = lds_first[0];
+        for (int w = 1; w < kHashWaves; ++w) m = lds_first[w] < m ? lds_first[w] : m;
+        mo.match_len[r] = m;
+      }
     }
   }
 }
@@ -297,6 +325,36 @@ __global__ __launch_bounds__(kGeneralWaves* kWave) void block_hash_general_kerne
 }  // namespace
 }  // namespace aibx
 
+namespace aibx {
+namespace {
+
+template <bool kMatch>
+int launch_hash(const int32_t* d_tokens, const int64_t* d_tok_off, const int64_t* d_blk_off, int32_t n_req,
+                int32_t block_size, u64 seed, u64* d_hash_out, MatchOut mo, hipStream_t st) {
+  // Thousands of requests: one wavefront each (no barrier, nothing idles on short requests).
+  // Few requests: four wavefronts each, so that a small batch finishes in fewer serial tiles.
+  const bool wide = n_req < 4096;
+  dim3 grid((u32)n_req);
+#define AIBX_LAUNCH_HASH(B)                                                                       \
+  if (wide)                                                                                       \
+    block_hash_pow2_kernel<B, 4, kMatch><<<grid, 4 * kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off, seed, \
+                                                                     d_hash_out, mo);            \
+  else                                                                                            \
+    block_hash_pow2_kernel<B, 1, kMatch><<<grid, kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off, seed,     \
+                                                                 d_hash_out, mo)
+  switch (block_size) {
+    case 16: AIBX_LAUNCH_HASH(16); break;
+    case 32: AIBX_LAUNCH_HASH(32); break;
+    case 64: AIBX_LAUNCH_HASH(64); break;
+    default: return AIBX_ERR_UNSUPPORTED;
+  }
+#undef AIBX_LAUNCH_HASH
+  return launch_status();
+}
+
+}  // namespace
+}  // namespace aibx
+
 extern "C" int aibx_block_hash(const int32_t* d_tokens, const int64_t* d_tok_off,
                                const int64_t* d_blk_off, int32_t n_req, int64_t n_blocks_total,
                                int32_t block_size, uint64_t seed, uint64_t* d_hash_out,
@@ -308,23 +366,38 @@ extern "C" int aibx_block_hash(const int32_t* d_tokens, const int64_t* d_tok_off
   if (!aligned(d_tokens, 4) || !aligned(d_tok_off, 8) || !aligned(d_blk_off, 8) || !aligned(d_hash_out, 8))
     return AIBX_ERR_ALIGN;
   hipStream_t st = as_stream(stream);
-  // Thousands of requests: one wavefront each (no barrier, nothing idles on short requests).
-  // Few requests: four wavefronts each, so that a small batch finishes in fewer serial tiles.
-  const bool wide = n_req < 4096;
-  dim3 grid((u32)n_req);
-#define AIBX_LAUNCH_HASH(B)                                                                              \
-  if (wide)                                                                                              \
-    block_hash_pow2_kernel<B, 4><<<grid, 4 * kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off, seed, d_hash_out); \
-  else                                                                                                   \
-    block_hash_pow2_kernel<B, 1><<<grid, kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off, seed, d_hash_out)
-  switch (block_size) {
-    case 16: AIBX_LAUNCH_HASH(16); break;
-    case 32: AIBX_LAUNCH_HASH(32); break;
-    case 64: AIBX_LAUNCH_HASH(64); break;
-    default:
-      block_hash_general_kernel<<<grid, kGeneralWaves * kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off, block_size,
-                                                                        seed, d_hash_out);
-  }
-#undef AIBX_LAUNCH_HASH
+  if (block_size == 16 || block_size == 32 || block_size == 64)
+    return launch_hash<false>(d_tokens, d_tok_off, d_blk_off, n_req, block_size, seed, d_hash_out, MatchOut{}, st);
+  block_hash_general_kernel<<<dim3((u32)n_req), kGeneralWaves * kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off,
+                                                                               block_size, seed, d_hash_out);
   return launch_status();
+}
+
+extern "C" int aibx_hash_match(const aibx_index_t* index, const int32_t* d_tokens, const int64_t* d_tok_off,
+                               const int64_t* d_blk_off, int32_t n_req, int64_t n_blocks_total,
+                               int32_t block_size, uint64_t seed, uint64_t* d_hash_out,
+                               uint64_t* d_values_out, int32_t* d_match_len, void* stream) {
+  using namespace aibx;
+  if (!index || n_req < 0 || n_blocks_total < 0 || block_size < 1 || block_size > 1024) return AIBX_ERR_INVALID_ARG;
+  if (n_req == 0) return AIBX_OK;
+  if (!d_tok_off || !d_blk_off || !d_match_len) return AIBX_ERR_INVALID_ARG;
+  if (n_blocks_total > 0 && !d_tokens) return AIBX_ERR_INVALID_ARG;
+  if (!aligned(d_tokens, 4) || !aligned(d_tok_off, 8) || !aligned(d_blk_off, 8) || !aligned(d_hash_out, 8) ||
+      !aligned(d_values_out, 8) || !aligned(d_match_len, 4))
+    return AIBX_ERR_ALIGN;
+  if (block_size != 16 && block_size != 32 && block_size != 64) {
+    // other block sizes: the two separate launches, which need the hash array as the hand-over
+    if (!d_hash_out) return AIBX_ERR_UNSUPPORTED;
+    const int rc = aibx_block_hash(d_tokens, d_tok_off, d_blk_off, n_req, n_blocks_total, block_size, seed,
+                                   d_hash_out, stream);
+    if (rc != AIBX_OK) return rc;
+    return aibx_prefix_match(index, d_hash_out, d_blk_off, n_req, n_blocks_total, d_values_out, d_match_len,
+                             stream);
+  }
+  MatchOut mo;
+  mo.table = table_of(index);
+  mo.values_out = d_values_out;
+  mo.match_len = d_match_len;
+  return launch_hash<true>(d_tokens, d_tok_off, d_blk_off, n_req, block_size, seed, d_hash_out, mo,
+                           as_stream(stream));
 }

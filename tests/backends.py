@@ -142,6 +142,21 @@ class HipIndex:
         return self._host_u64(values), mlen.cpu().numpy()
 
 
+def hip_hash_match(ix, tokens, tok_off, blk_off, block_size, seed, want_hashes=True, want_values=True):
+    """aibx_hash_match on host arrays: (hashes or None, values or None, match_len)."""
+    t, a = ix.t, ix.a
+    d_tok = t.from_numpy(np.ascontiguousarray(tokens, dtype=np.int32).copy()).cuda()
+    d_to = t.from_numpy(np.ascontiguousarray(tok_off, dtype=np.int64).copy()).cuda()
+    d_bo = t.from_numpy(np.ascontiguousarray(blk_off, dtype=np.int64).copy()).cuda()
+    n_req, n = len(tok_off) - 1, int(blk_off[-1])
+    h = t.full((n,), -3, dtype=t.int64, device="cuda") if want_hashes else None
+    v = t.full((n,), -5, dtype=t.int64, device="cuda") if want_values else None
+    m = t.full((max(n_req, 0),), -7, dtype=t.int32, device="cuda")
+    a.aibx_hash_match(ix.h, d_tok, d_to, d_bo, n_req, n, block_size, seed, h, v, m)
+    u = lambda x: None if x is None else x.cpu().numpy().view(np.uint64)
+    return u(h), u(v), m.cpu().numpy()
+
+
 class HipBackend:
     """The HIP library through its Python binding; host arrays in, host arrays out."""
     name = "hip"

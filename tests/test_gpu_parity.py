@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 import oracle
-from backends import HipBackend, HipIndex, OracleBackend
+from backends import HipBackend, HipIndex, OracleBackend, hip_hash_match
 from workloads import Geometry, make_tokens, make_workload, flows
 
 pytestmark = pytest.mark.gpu
@@ -262,6 +262,39 @@ def test_match_edge_cases():
     ov, om = oi.match(h, blk_off)
     assert np.array_equal(gv, ov) and np.array_equal(gm, om)
     assert gm[4] >= 130
+
+
+# ---- hash + match in one launch -------------------------------------------------------------------
+@pytest.mark.parametrize("B,n_req", [(16, 37), (32, 21), (64, 19), (16, 5000), (64, 4500), (24, 11)])
+def test_hash_match_equals_hash_then_match(B, n_req):
+    """Few requests (4 wavefronts each), thousands (1 wavefront each), and a block size that runs
+    as two launches; half of the requests are indexed, a slice of their blocks evicted again."""
+    rng = np.random.default_rng(B * 7 + n_req)
+    tok, tok_off, lens = _ragged(rng, n_req, 0, 30 * B if n_req > 1000 else 150 * B)
+    lens[1] = 0
+    lens[2] = B - 1
+    np.cumsum(lens, out=tok_off[1:])
+    tok = rng.integers(0, 32000, size=int(tok_off[-1]), dtype=np.int32)
+    # requests come in pairs that share a prefix of the first of the two
+    for r in range(1, n_req, 2):
+        k = min(int(lens[r]), int(lens[r - 1])) * 2 // 3
+        tok[tok_off[r]:tok_off[r] + k] = tok[tok_off[r - 1]:tok_off[r - 1] + k]
+    blk_off = np.zeros(n_req + 1, dtype=np.int64)
+    np.cumsum(lens // B, out=blk_off[1:])
+    want_h = oracle.block_hash(tok, tok_off, blk_off, B, 11)
+    gi, oi = HipIndex(1 << 18), oracle.Index(1 << 18)
+    cached = np.concatenate([want_h[blk_off[r]:blk_off[r + 1]] for r in range(0, n_req, 2)] + [want_h[:0]])
+    cached = np.unique(cached)
+    for ix in (gi, oi):
+        ix.insert(cached, cached >> np.uint64(9))
+        ix.evict(cached[::17])
+    want_v, want_m = oi.match(want_h, blk_off)
+    h, v, m = hip_hash_match(gi, tok, tok_off, blk_off, B, 11)
+    assert np.array_equal(h, want_h) and np.array_equal(v, want_v) and np.array_equal(m, want_m)
+    if B != 24:
+        h2, v2, m2 = hip_hash_match(gi, tok, tok_off, blk_off, B, 11, want_hashes=False, want_values=False)
+        assert h2 is None and v2 is None and np.array_equal(m2, want_m)
+    assert want_m.max() > 0
 
 
 # ---- gather / scatter --------------------------------------------------------------------------
