@@ -9,6 +9,7 @@
  *   aibx_block_hash    chained per-block hashes of request token streams
  *   aibx_prefix_match  lookup of those hashes in a GPU-resident cache index + first-miss length
  *   aibx_hash_match    the two above in one launch
+ *   aibx_route         per request: the pod with the longest cached prefix, if above a threshold
  *   aibx_index_insert  metadata update: (key -> value) upsert           (Section 3.2.5)
  *   aibx_index_evict   metadata update: removal of evicted keys          (Section 3.2.5)
  *   aibx_kv_gather     paged KV pool -> contiguous staging (offload)     (Section 3.2.5)
@@ -171,6 +172,27 @@ int aibx_hash_match(const aibx_index_t* index, const int32_t* d_tokens, const in
                     const int64_t* d_blk_off, int32_t n_req, int64_t n_blocks_total,
                     int32_t block_size, uint64_t seed, uint64_t* d_hash_out,
                     uint64_t* d_values_out, int32_t* d_match_len, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Prefix-cache-aware routing decision.  (Section 3.2.2: the policy "prioritizes instances with
+ * reusable prefix cache, with a cache hit exceeding the threshold"; below the threshold it falls
+ * back to the least-request policy of the same list.)
+ * The index value of a block is read as the SET OF PODS holding it: bit p = pod p, p < n_pods <= 63
+ * (AIBX_NO_VALUE = no pod; higher bits are ignored). d_pod_sets is the per-block output of
+ * aibx_prefix_match / aibx_hash_match. For request r with n_r blocks and pod p,
+ *   len_p = number of leading blocks of r whose set contains p,   best = max_p len_p.
+ * If n_r > 0, best > 0 and best/n_r >= threshold_num/threshold_den (compared as integers,
+ * best*den >= num*n_r), the candidates are the pods with len_p = best; otherwise every pod is a
+ * candidate. The request goes to the candidate with the smallest d_pod_load (admitted requests),
+ * ties to the smallest pod id: d_pod_out[r] = that pod, d_hit_len_out[r] = its len_p.
+ * Loads are read once; requests of one batch do not see each other's assignment.
+ *   d_pod_sets uint64[n_blocks_total]; d_blk_off int64[n_req+1]; d_pod_load int32[n_pods], >= 0;
+ *   threshold_num, threshold_den < 2^32, den > 0; d_pod_out, d_hit_len_out int32[n_req].
+ * Errors: INVALID_ARG, ALIGN, HIP. */
+int aibx_route(const uint64_t* d_pod_sets, const int64_t* d_blk_off, int32_t n_req,
+               int64_t n_blocks_total, int32_t n_pods, const int32_t* d_pod_load,
+               uint64_t threshold_num, uint64_t threshold_den, int32_t* d_pod_out,
+               int32_t* d_hit_len_out, void* stream);
 
 /* ------------------------------------------------------------------------------------------
  * Paged-KV gather / scatter.  (Moving KV blocks between the engine's paged memory and the

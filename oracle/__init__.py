@@ -62,6 +62,8 @@ def _load():
         for f in (lib.orc_kv_gather, lib.orc_kv_scatter):
             f.argtypes = [C.POINTER(_PoolDesc), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
                           C.c_uint64, C.c_void_p]
+        lib.orc_route.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_uint64,
+                                  C.c_uint64, C.c_void_p, C.c_void_p]
         for f in (lib.orc_finalise, lib.orc_avoid_reserved):
             f.argtypes = [C.c_uint64]
             f.restype = C.c_uint64
@@ -165,6 +167,22 @@ class Index:
                                         _ptr(values), _ptr(mlen))
         assert rc == 0
         return values, mlen
+
+
+def route(pod_sets, blk_off, n_pods: int, pod_load, thr_num: int, thr_den: int):
+    """(pod int32[R], hit_len int32[R]): prefix-cache-aware choice with least-request fallback."""
+    pod_sets = _arr(pod_sets, np.uint64)
+    blk_off = _arr(blk_off, np.int64)
+    pod_load = _arr(pod_load, np.int32)
+    assert len(pod_load) == n_pods
+    n_req = len(blk_off) - 1
+    pod = np.empty(max(n_req, 0), dtype=np.int32)
+    hit = np.empty(max(n_req, 0), dtype=np.int32)
+    rc = _load().orc_route(_ptr(pod_sets), _ptr(blk_off), n_req, int(n_pods), _ptr(pod_load),
+                           C.c_uint64(thr_num), C.c_uint64(thr_den), _ptr(pod), _ptr(hit))
+    if rc != 0:
+        raise ValueError(f"orc_route: invalid arguments (rc={rc})")
+    return pod, hit
 
 
 def _desc(pool: np.ndarray, n_seg, seg_stride, page_stride, seg_bytes, n_pages):

@@ -203,6 +203,39 @@ int orc_prefix_match(const void* h, const u64* hashes, const int64_t* blk_off, i
 }
 
 // ---------------------------------------------------------------------------------------------
+// Prefix-cache-aware routing decision (Section 3.2.2: route to an instance with a reusable prefix
+// cache if the hit exceeds a threshold).
+// reading: a block's index value is the set of pods holding it (bit p = pod p, p < n_pods <= 63;
+// kNoValue = none). For request r and pod p, len_p = number of leading blocks whose set contains p.
+// reading: best = max_p len_p; if n_r > 0, best > 0 and best*den >= num*n_r the candidates are the
+// pods with len_p == best, otherwise (fallback: the least-request policy of the same list) every
+// pod; among the candidates the smallest load wins, ties to the smallest pod id.
+int orc_route(const u64* pod_sets, const int64_t* blk_off, int32_t n_req, int32_t n_pods,
+              const int32_t* pod_load, u64 thr_num, u64 thr_den, int32_t* pod_out, int32_t* hit_len_out) {
+  if (n_req < 0 || n_pods < 1 || n_pods > 63 || thr_den == 0) return -1;
+  std::vector<int64_t> len(n_pods);
+  for (int32_t r = 0; r < n_req; ++r) {
+    const int64_t b0 = blk_off[r], n_r = blk_off[r + 1] - blk_off[r];
+    int64_t best = 0;
+    for (int32_t p = 0; p < n_pods; ++p) {
+      int64_t j = 0;
+      while (j < n_r && pod_sets[b0 + j] != kNoValue && ((pod_sets[b0 + j] >> p) & 1ull)) ++j;
+      len[p] = j;
+      best = std::max(best, j);
+    }
+    const bool aware = n_r > 0 && best > 0 && (u64)best * thr_den >= thr_num * (u64)n_r;
+    int32_t chosen = -1;
+    for (int32_t p = 0; p < n_pods; ++p) {
+      if (aware && len[p] != best) continue;
+      if (chosen < 0 || pod_load[p] < pod_load[chosen]) chosen = p;
+    }
+    pod_out[r] = chosen;
+    hit_len_out[r] = (int32_t)len[chosen];
+  }
+  return 0;
+}
+
+// ---------------------------------------------------------------------------------------------
 // Paged-KV gather / scatter (moving KV blocks between the engine's paged memory and the cache's
 // contiguous buffers, Section 3.2.5). Pure byte copies.
 //

@@ -16,7 +16,7 @@ EXPORTS = [
     "aibx_version", "aibx_hash_version", "aibx_strerror", "aibx_last_hip_error",
     "aibx_block_hash", "aibx_index_storage_bytes", "aibx_index_create", "aibx_index_destroy",
     "aibx_index_clear", "aibx_index_insert", "aibx_index_evict", "aibx_index_count",
-    "aibx_index_dump", "aibx_prefix_match", "aibx_hash_match", "aibx_kv_gather", "aibx_kv_scatter",
+    "aibx_index_dump", "aibx_prefix_match", "aibx_hash_match", "aibx_route", "aibx_kv_gather", "aibx_kv_scatter",
 ]
 
 
@@ -65,6 +65,7 @@ def load(build_if_missing: bool = True):
     lib.aibx_index_count.argtypes = [vp, vp, vp]
     lib.aibx_index_dump.argtypes = [vp, vp, vp, u64, vp, vp]
     lib.aibx_prefix_match.argtypes = [vp, vp, vp, i32, i64, vp, vp, vp]
+    lib.aibx_route.argtypes = [vp, vp, i32, i64, i32, vp, u64, u64, vp, vp, vp]
     lib.aibx_hash_match.argtypes = [vp, vp, vp, vp, i32, i64, i32, u64, vp, vp, vp, vp]
     for f in (lib.aibx_kv_gather, lib.aibx_kv_scatter):
         f.argtypes = [C.POINTER(PoolDesc), vp, vp, i64, vp, u64, vp, vp]
@@ -173,6 +174,14 @@ def aibx_hash_match(index, d_tokens, d_tok_off, d_blk_off, n_req, n_blocks_total
         index, _p(d_tokens, torch.int32), _p(d_tok_off, torch.int64), _p(d_blk_off, torch.int64),
         int(n_req), int(n_blocks_total), int(block_size), C.c_uint64(int(seed) & AIBX_NO_VALUE),
         _p(d_hash_out, U64), _p(d_values_out, U64), _p(d_match_len, torch.int32), _s(stream)))
+
+
+def aibx_route(d_pod_sets, d_blk_off, n_req, n_blocks_total, n_pods, d_pod_load, threshold_num,
+               threshold_den, d_pod_out, d_hit_len_out, stream=None):
+    _check("aibx_route", load().aibx_route(
+        _p(d_pod_sets, U64), _p(d_blk_off, torch.int64), int(n_req), int(n_blocks_total), int(n_pods),
+        _p(d_pod_load, torch.int32), int(threshold_num), int(threshold_den),
+        _p(d_pod_out, torch.int32), _p(d_hit_len_out, torch.int32), _s(stream)))
 
 
 def make_pool_desc(d_pool, n_seg, seg_stride, page_stride, seg_bytes, n_pages) -> PoolDesc:

@@ -68,6 +68,12 @@ def test_argument_errors_are_raised_before_any_launch(lib):
     assert lib.aibx_prefix_match(None, fake, fake, 1, 1, None, fake, None) == -1
     assert lib.aibx_index_destroy(None) == 0
     assert lib.aibx_hash_match(None, fake, fake, fake, 1, 1, 16, 0, fake, fake, fake, None) == -1
+    # routing
+    assert lib.aibx_route(fake, fake, 1, 1, 0, fake, 1, 2, fake, fake, None) == -1
+    assert lib.aibx_route(fake, fake, 1, 1, 64, fake, 1, 2, fake, fake, None) == -1
+    assert lib.aibx_route(fake, fake, 1, 1, 8, fake, 1, 0, fake, fake, None) == -1
+    assert lib.aibx_route(fake, fake, 0, 0, 8, fake, 1, 2, fake, fake, None) == 0
+    assert lib.aibx_route(fake, odd, 1, 1, 8, fake, 1, 2, fake, fake, None) == -2
     # copies
     d = PoolDesc(0x1000, 2, 1 << 20, 4096, 4096, 16)
     assert lib.aibx_kv_gather(C.byref(d), fake, None, -1, fake, 8192, None, None) == -1

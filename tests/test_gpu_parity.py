@@ -297,6 +297,40 @@ def test_hash_match_equals_hash_then_match(B, n_req):
     assert want_m.max() > 0
 
 
+# ---- routing decision -----------------------------------------------------------------------------
+@pytest.mark.parametrize("n_pods,num,den", [(1, 1, 2), (7, 0, 1), (7, 1, 2), (7, 9, 10), (63, 1, 3), (63, 2, 1)])
+def test_route_parity(n_pods, num, den):
+    import torch
+    import paper_2504_03648_amd as aibx
+    rng = np.random.default_rng(n_pods * 100 + num)
+    n_req = 300
+    sizes = rng.integers(0, 400, size=n_req)
+    sizes[:4] = [0, 1, 64, 65]
+    blk_off = np.zeros(n_req + 1, dtype=np.int64)
+    np.cumsum(sizes, out=blk_off[1:])
+    n = int(blk_off[-1])
+    all_pods = (1 << n_pods) - 1
+    sets = np.zeros(n, dtype=np.uint64)
+    for r in range(n_req):
+        # a few pods hold a long prefix each, the rest is sparse noise
+        k = int(sizes[r])
+        row = rng.integers(0, 1 << min(n_pods, 62), size=k, dtype=np.uint64) & rng.integers(0, 1 << min(n_pods, 62), size=k, dtype=np.uint64)
+        for p in rng.integers(0, n_pods, size=3):
+            row[: int(rng.integers(0, k + 1))] |= np.uint64(1) << np.uint64(p)
+        sets[blk_off[r]:blk_off[r + 1]] = row & np.uint64(all_pods)
+    sets[rng.random(n) < 0.01] = NO
+    load = rng.integers(0, 5, size=n_pods).astype(np.int32)
+    want_pod, want_hit = oracle.route(sets, blk_off, n_pods, load, num, den)
+    d_sets = torch.from_numpy(sets.view(np.int64).copy()).cuda()
+    d_bo = torch.from_numpy(blk_off).cuda()
+    d_load = torch.from_numpy(load).cuda()
+    pod = torch.full((n_req,), -9, dtype=torch.int32, device="cuda")
+    hit = torch.full((n_req,), -9, dtype=torch.int32, device="cuda")
+    aibx.aibx_route(d_sets, d_bo, n_req, n, n_pods, d_load, num, den, pod, hit)
+    assert np.array_equal(pod.cpu().numpy(), want_pod) and np.array_equal(hit.cpu().numpy(), want_hit)
+    assert want_hit.max() > 64
+
+
 # ---- gather / scatter --------------------------------------------------------------------------
 @pytest.mark.parametrize("n_seg,seg_bytes,n_pages,n", [
     (1, 262144, 40, 23), (64, 32768, 24, 17), (61, 73728, 12, 9), (5, 16, 50, 33),
