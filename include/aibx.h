@@ -12,6 +12,7 @@
  *   aibx_route         per request: the pod with the longest cached prefix, if above a threshold
  *   aibx_index_insert  metadata update: (key -> value) upsert           (Section 3.2.5)
  *   aibx_index_evict   metadata update: removal of evicted keys          (Section 3.2.5)
+ *   aibx_index_touch / _age / _select_victims   scan-resistant victim selection (Section 3.2.5)
  *   aibx_kv_gather     paged KV pool -> contiguous staging (offload)     (Section 3.2.5)
  *   aibx_kv_scatter    contiguous staging -> paged KV pool (onload)      (Section 3.2.5)
  *
@@ -104,7 +105,8 @@ int aibx_block_hash(const int32_t* d_tokens, const int64_t* d_tok_off, const int
  */
 typedef struct aibx_index aibx_index_t; /* opaque host handle */
 
-/* Bytes of device storage a table of n_slots needs. n_slots: power of two, 8 <= n_slots <= 2^36.
+/* Bytes of device storage a table of n_slots needs (20 per slot: the 16-byte slot and a 4-byte
+ * usage word). n_slots: power of two, 8 <= n_slots <= 2^36.
  * Errors: INVALID_ARG (null out), UNSUPPORTED. */
 int aibx_index_storage_bytes(uint64_t n_slots, size_t* out_bytes);
 
@@ -136,6 +138,29 @@ int aibx_index_insert(aibx_index_t* index, const uint64_t* d_keys, const uint64_
  * Errors: INVALID_ARG, ALIGN, HIP. */
 int aibx_index_evict(aibx_index_t* index, const uint64_t* d_keys, int64_t n,
                      uint64_t* d_values_out, uint64_t* d_counters2, void* stream);
+
+/* Usage tracking and victim selection.  (Section 3.2.5 names a "scan-resistant eviction policy"
+ * that "selectively persist[s] hot KV tensors" and does not describe it; this is the rule here.)
+ * Every indexed key carries a touch count and the last epoch it was touched in; a newly inserted
+ * key has count 0 and epoch 0, an upsert of a present key keeps its usage, eviction discards it.
+ *   aibx_index_touch: for each i < n, if d_keys[i] is present its count goes up by one (saturating
+ *     at 255) and its last epoch becomes max(last, epoch); absent and reserved keys are ignored; a
+ *     key named k times in a batch is touched k times. `epoch` is the caller's logical clock,
+ *     0 <= epoch < 2^24. The caller reports the blocks a request actually reused.
+ *   aibx_index_age: halves every count (call it once per ageing period).
+ *   aibx_index_select_victims: writes, in no particular order, every live (key, value) with
+ *     count < protect_count AND last < before_epoch, and their number to *d_n_out (the call
+ *     resets it; pairs beyond `capacity` are counted but not written). With protect_count = 2 a
+ *     block brought in by a one-off scan (touched at most once) goes as soon as it is older than
+ *     before_epoch, while a block that was reused stays until ageing has worn its count down.
+ *     The victims then go to aibx_kv_gather (offload) and aibx_index_evict.
+ * Errors: INVALID_ARG (also epoch >= 2^24), ALIGN, HIP. */
+int aibx_index_touch(aibx_index_t* index, const uint64_t* d_keys, int64_t n, uint32_t epoch,
+                     void* stream);
+int aibx_index_age(aibx_index_t* index, void* stream);
+int aibx_index_select_victims(const aibx_index_t* index, uint32_t protect_count,
+                              uint32_t before_epoch, uint64_t* d_keys_out, uint64_t* d_values_out,
+                              uint64_t capacity, uint64_t* d_n_out, void* stream);
 
 /* *d_live_out (device uint64) = number of keys in the index. */
 int aibx_index_count(const aibx_index_t* index, uint64_t* d_live_out, void* stream);

@@ -62,6 +62,12 @@ def _load():
         for f in (lib.orc_kv_gather, lib.orc_kv_scatter):
             f.argtypes = [C.POINTER(_PoolDesc), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
                           C.c_uint64, C.c_void_p]
+        lib.orc_index_touch.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_uint32]
+        lib.orc_index_age.argtypes = [C.c_void_p]
+        lib.orc_index_age.restype = None
+        lib.orc_index_select_victims.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p,
+                                                 C.c_uint64]
+        lib.orc_index_select_victims.restype = C.c_uint64
         lib.orc_route.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_uint64,
                                   C.c_uint64, C.c_void_p, C.c_void_p]
         for f in (lib.orc_finalise, lib.orc_avoid_reserved):
@@ -155,6 +161,23 @@ class Index:
         m = self._lib.orc_index_dump(self._h, _ptr(k), _ptr(v), n)
         assert m == n
         return k, v
+
+    def touch(self, keys, epoch: int):
+        keys = _arr(keys, np.uint64)
+        rc = self._lib.orc_index_touch(self._h, _ptr(keys), len(keys), int(epoch))
+        assert rc == 0
+
+    def age(self):
+        self._lib.orc_index_age(self._h)
+
+    def select_victims(self, protect_count: int, before_epoch: int):
+        """(keys, values) of the victims, sorted by key."""
+        cap = self.count()
+        k = np.empty(cap, dtype=np.uint64)
+        v = np.empty(cap, dtype=np.uint64)
+        m = int(self._lib.orc_index_select_victims(self._h, int(protect_count), int(before_epoch),
+                                                   _ptr(k), _ptr(v), cap))
+        return k[:m].copy(), v[:m].copy()
 
     def match(self, hashes, blk_off):
         """(values uint64[N], match_len int32[R]) under the first-miss rule."""

@@ -60,9 +60,15 @@ u64 avoid_reserved(u64 h) {
   return (h == kEmptyKey || h == kTombKey) ? (h ^ kPhi) : h;
 }
 
+struct Usage {
+  uint32_t count;   // touches since insertion (saturating at 255), halved by ageing
+  uint32_t last;    // largest epoch the key was touched in (0 = never)
+};
+
 struct Index {
   u64 capacity;
-  std::unordered_map<u64, u64> map;    // abstract key -> value map; no slots, no probing
+  std::unordered_map<u64, u64> map;      // abstract key -> value map; no slots, no probing
+  std::unordered_map<u64, Usage> usage;  // same keys as `map`
 };
 
 }  // namespace
@@ -124,7 +130,10 @@ void* orc_index_create(u64 n_slots) {
 
 void orc_index_destroy(void* h) { delete static_cast<Index*>(h); }
 
-void orc_index_clear(void* h) { static_cast<Index*>(h)->map.clear(); }
+void orc_index_clear(void* h) {
+  static_cast<Index*>(h)->map.clear();
+  static_cast<Index*>(h)->usage.clear();
+}
 
 // Batch upsert, applied in array order. counters3 accumulates {inserted, updated, full}.
 // reading: absent key -> added (inserted); present key -> value overwritten (updated);
@@ -141,6 +150,7 @@ int orc_index_insert(void* h, const u64* keys, const u64* values, int64_t n, u64
     if (it != ix->map.end()) { it->second = values[i]; ++updated; continue; }
     if (ix->map.size() >= ix->capacity) { ++full; continue; }
     ix->map.emplace(k, values[i]);
+    ix->usage[k] = Usage{0, 0};          // a new key starts untouched
     ++inserted;
   }
   if (counters3) { counters3[0] += inserted; counters3[1] += updated; counters3[2] += full; }
@@ -156,12 +166,52 @@ int orc_index_evict(void* h, const u64* keys, int64_t n, u64* values_out, u64* c
   for (int64_t i = 0; i < n; ++i) {
     u64 v = kNoValue;
     auto it = ix->map.find(keys[i]);
-    if (it != ix->map.end()) { v = it->second; ix->map.erase(it); ++evicted; }
+    if (it != ix->map.end()) { v = it->second; ix->map.erase(it); ix->usage.erase(keys[i]); ++evicted; }
     else ++missing;
     if (values_out) values_out[i] = v;
   }
   if (counters2) { counters2[0] += evicted; counters2[1] += missing; }
   return 0;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Usage tracking and victim selection (Section 3.2.5 names a "scan-resistant eviction policy" that
+// keeps hot KV and does not describe it).
+// reading: every indexed key carries a touch count and the last epoch it was touched in. A touch
+// (the caller reports the blocks a request actually reused, with its logical clock `epoch`) adds
+// one to the count, saturating at 255, and raises `last` to `epoch`; absent keys are ignored; a key
+// named several times in one batch is touched that many times. Ageing halves every count.
+// Victims are the keys with count < protect_count AND last < before_epoch: a block brought in by a
+// one-off scan has been touched at most once and goes as soon as it is old, while a block that
+// was reused keeps a count >= 2 until ageing wears it down. Upserting a present key keeps its usage.
+int orc_index_touch(void* h, const u64* keys, int64_t n, uint32_t epoch) {
+  if (!h || n < 0 || epoch > 0xFFFFFFu) return -1;
+  Index* ix = static_cast<Index*>(h);
+  for (int64_t i = 0; i < n; ++i) {
+    auto it = ix->usage.find(keys[i]);
+    if (it == ix->usage.end()) continue;
+    if (it->second.count < 255) ++it->second.count;
+    it->second.last = std::max(it->second.last, epoch);
+  }
+  return 0;
+}
+
+void orc_index_age(void* h) {
+  for (auto& kv : static_cast<Index*>(h)->usage) kv.second.count >>= 1;
+}
+
+// Victims in ascending key order; returns their number (which may exceed `capacity`).
+u64 orc_index_select_victims(const void* h, uint32_t protect_count, uint32_t before_epoch, u64* keys_out,
+                             u64* values_out, u64 capacity) {
+  const Index* ix = static_cast<const Index*>(h);
+  std::vector<std::pair<u64, u64>> out;
+  for (const auto& kv : ix->usage)
+    if (kv.second.count < protect_count && kv.second.last < before_epoch)
+      out.emplace_back(kv.first, ix->map.at(kv.first));
+  std::sort(out.begin(), out.end());
+  const u64 m = std::min<u64>(capacity, out.size());
+  for (u64 i = 0; i < m; ++i) { keys_out[i] = out[i].first; values_out[i] = out[i].second; }
+  return out.size();
 }
 
 u64 orc_index_count(const void* h) { return static_cast<const Index*>(h)->map.size(); }

@@ -16,7 +16,8 @@ EXPORTS = [
     "aibx_version", "aibx_hash_version", "aibx_strerror", "aibx_last_hip_error",
     "aibx_block_hash", "aibx_index_storage_bytes", "aibx_index_create", "aibx_index_destroy",
     "aibx_index_clear", "aibx_index_insert", "aibx_index_evict", "aibx_index_count",
-    "aibx_index_dump", "aibx_prefix_match", "aibx_hash_match", "aibx_route", "aibx_kv_gather", "aibx_kv_scatter",
+    "aibx_index_dump", "aibx_index_touch", "aibx_index_age", "aibx_index_select_victims",
+    "aibx_prefix_match", "aibx_hash_match", "aibx_route", "aibx_kv_gather", "aibx_kv_scatter",
 ]
 
 
@@ -65,6 +66,9 @@ def load(build_if_missing: bool = True):
     lib.aibx_index_count.argtypes = [vp, vp, vp]
     lib.aibx_index_dump.argtypes = [vp, vp, vp, u64, vp, vp]
     lib.aibx_prefix_match.argtypes = [vp, vp, vp, i32, i64, vp, vp, vp]
+    lib.aibx_index_touch.argtypes = [vp, vp, i64, C.c_uint32, vp]
+    lib.aibx_index_age.argtypes = [vp, vp]
+    lib.aibx_index_select_victims.argtypes = [vp, C.c_uint32, C.c_uint32, vp, vp, u64, vp, vp]
     lib.aibx_route.argtypes = [vp, vp, i32, i64, i32, vp, u64, u64, vp, vp, vp]
     lib.aibx_hash_match.argtypes = [vp, vp, vp, vp, i32, i64, i32, u64, vp, vp, vp, vp]
     for f in (lib.aibx_kv_gather, lib.aibx_kv_scatter):
@@ -159,6 +163,21 @@ def aibx_index_dump(index, d_keys_out, d_values_out, capacity, d_n_out, stream=N
     _check("aibx_index_dump", load().aibx_index_dump(
         index, _p(d_keys_out, U64), _p(d_values_out, U64), int(capacity), _p(d_n_out, U64),
         _s(stream)))
+
+
+def aibx_index_touch(index, d_keys, n, epoch, stream=None):
+    _check("aibx_index_touch", load().aibx_index_touch(index, _p(d_keys, U64), int(n), int(epoch), _s(stream)))
+
+
+def aibx_index_age(index, stream=None):
+    _check("aibx_index_age", load().aibx_index_age(index, _s(stream)))
+
+
+def aibx_index_select_victims(index, protect_count, before_epoch, d_keys_out, d_values_out, capacity,
+                              d_n_out, stream=None):
+    _check("aibx_index_select_victims", load().aibx_index_select_victims(
+        index, int(protect_count), int(before_epoch), _p(d_keys_out, U64), _p(d_values_out, U64),
+        int(capacity), _p(d_n_out, U64), _s(stream)))
 
 
 def aibx_prefix_match(index, d_hashes, d_blk_off, n_req, n_blocks_total, d_values_out,

@@ -2,6 +2,8 @@
 // metadata updates", Section 3.2.5 of the paper; the reusable-prefix test of the
 // prefix-cache-aware policy, Section 3.2.2). Semantics are stated in aibx.h.
 //
+// Behind the slots the storage holds one 32-bit usage word per slot (touch count and last epoch)
+// for the victim selection of the eviction policy.
 // Table: open addressing over buckets of 8 slots; a slot is {u64 key, u64 value}, so a bucket is
 // one 128-byte line. Key 0 = EMPTY, key 2^64-1 = TOMBSTONE. A key lives in the first bucket of
 // its probe sequence (home, home+step, home+2*step, ... mod n_buckets, step odd and key-dependent)
@@ -158,6 +160,7 @@ __global__ __launch_bounds__(kIndexThreads) void index_insert_kernel(
                                 (unsigned long long)key);
       if (old == cand_expected) {  // the slot is ours
         store_value(cslot + 1, val);
+        t.usage[cand_bucket * kBucket + cand_slot] = 0;  // a new key starts untouched
         ++n_ins;
         break;
       }
@@ -241,6 +244,87 @@ __global__ __launch_bounds__(kIndexThreads) void index_evict_kernel(
   }
 }
 
+// ---- usage tracking and victim selection -------------------------------------------------------
+// (the "scan-resistant eviction policy" of Section 3.2.5; the rule is stated in aibx.h)
+// touch: one lane per key; finds the key's slot like a lookup and bumps its usage word with a
+// compare-and-swap loop (count saturates at 255, epoch only moves forward).
+__global__ __launch_bounds__(kIndexThreads) void index_touch_kernel(Table t, const u64* __restrict__ keys,
+                                                                   int64_t n, u32 epoch) {
+  for (int64_t i = (int64_t)blockIdx.x * kIndexThreads + threadIdx.x; i < n; i += (int64_t)gridDim.x * kIndexThreads) {
+    const u64 key = keys[i];
+    if (key == kEmpty || key == kTomb) continue;
+    const u64 step = probe_step(key);
+    u64 b = home_bucket(t, key);
+    for (u64 seen_buckets = 0;; ++seen_buckets) {
+      const slot_t* bucket = reinterpret_cast<const slot_t*>(t.slots + 2 * b * kBucket);
+      int hit = -1;
+      bool ends = seen_buckets >= t.bucket_mask;
+#pragma unroll
+      for (int j = 0; j < kBucket; ++j) {
+        const u64 k = bucket[j].x;
+        if (k == key) hit = j;
+        ends |= k == kEmpty;
+      }
+      if (hit >= 0) {
+        u32* word = t.usage + b * kBucket + hit;
+        u32 seen = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (;;) {  // ends: every failed swap means another touch of this key went through
+          const u32 count = seen >> 24, last = seen & kEpochMask;
+          const u32 want = ((count < 255 ? count + 1 : 255u) << 24) | (epoch > last ? epoch : last);
+          const u32 old = atomicCAS(word, seen, want);
+          if (old == seen) break;
+          seen = old;
+        }
+        break;
+      }
+      if (ends) break;
+      b = (b + step) & t.bucket_mask;
+    }
+  }
+}
+
+// age: halves every touch count (one streaming pass over the usage words).
+__global__ __launch_bounds__(kIndexThreads) void index_age_kernel(u32* usage, u64 n_slots) {
+  for (u64 i = (u64)blockIdx.x * kIndexThreads + threadIdx.x; i < n_slots; i += (u64)gridDim.x * kIndexThreads) {
+    const u32 w = usage[i];
+    usage[i] = ((w >> 25) << 24) | (w & kEpochMask);
+  }
+}
+
+// victims: streams over the table and emits every live key whose touch count is below
+// `protect_count` and whose last epoch is before `before_epoch`; positions come from one atomic
+// per wavefront.
+__global__ __launch_bounds__(kIndexThreads) void index_victims_kernel(const u64* slots, const u32* usage,
+                                                                     u64 n_slots, u32 protect_count,
+                                                                     u32 before_epoch, u64* keys_out,
+                                                                     u64* values_out, u64 capacity, u64* n_out) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const u64 stride = (u64)gridDim.x * kIndexThreads;
+  for (u64 i0 = (u64)blockIdx.x * kIndexThreads + (threadIdx.x - lane); i0 < n_slots; i0 += stride) {
+    const u64 i = i0 + lane;
+    u64 k = kEmpty, v = 0;
+    u32 w = ~0u;
+    if (i < n_slots) {
+      k = slots[2 * i];
+      v = slots[2 * i + 1];
+      w = usage[i];
+    }
+    const bool cold = k != kEmpty && k != kTomb && (w >> 24) < protect_count && (w & kEpochMask) < before_epoch;
+    const u64 mask = __ballot(cold);
+    if (mask == 0) continue;
+    u64 start = 0;
+    if (lane == 0) start = atomicAdd((unsigned long long*)n_out, (unsigned long long)__popcll(mask));
+    start = shfl64(start, 0);
+    if (cold) {
+      const u64 pos = start + __popcll(mask & ((1ull << lane) - 1ull));
+      if (pos < capacity) {
+        keys_out[pos] = k;
+        values_out[pos] = v;
+      }
+    }
+  }
+}
+
 // ---- whole-table passes ------------------------------------------------------------------------
 __global__ __launch_bounds__(kIndexThreads) void fill_zero_kernel(uint4* p, u64 n_vec) {
   for (u64 i = (u64)blockIdx.x * kIndexThreads + threadIdx.x; i < n_vec; i += (u64)gridDim.x * kIndexThreads)
@@ -309,13 +393,13 @@ int aibx_index_storage_bytes(uint64_t n_slots, size_t* out_bytes) {
   if (!out_bytes) return AIBX_ERR_INVALID_ARG;
   const int rc = check_slots(n_slots);
   if (rc != AIBX_OK) return rc;
-  *out_bytes = (size_t)n_slots * 16;
+  *out_bytes = (size_t)n_slots * (kSlotBytes + kUsageBytes);
   return AIBX_OK;
 }
 
 int aibx_index_clear(aibx_index_t* index, void* stream) {
   if (!index) return AIBX_ERR_INVALID_ARG;
-  const u64 n_vec = index->n_slots;  // one 16-byte vector per slot
+  const u64 n_vec = index->n_slots * (kSlotBytes + kUsageBytes) / 16;  // slots and usage words
   fill_zero_kernel<<<pass_grid(n_vec), kIndexThreads, 0, as_stream(stream)>>>(
       reinterpret_cast<uint4*>(index->slots), n_vec);
   return launch_status();
@@ -327,10 +411,11 @@ int aibx_index_create(void* d_storage, size_t bytes, uint64_t n_slots, void* str
   *out = nullptr;
   const int rc = check_slots(n_slots);
   if (rc != AIBX_OK) return rc;
-  if (bytes < (size_t)n_slots * 16) return AIBX_ERR_INVALID_ARG;
+  if (bytes < (size_t)n_slots * (kSlotBytes + kUsageBytes)) return AIBX_ERR_INVALID_ARG;
   if (!aligned(d_storage, 256)) return AIBX_ERR_ALIGN;
   aibx_index* ix = new aibx_index();
   ix->slots = static_cast<u64*>(d_storage);
+  ix->usage = reinterpret_cast<u32*>(ix->slots + 2 * n_slots);
   ix->n_slots = n_slots;
   ix->n_buckets = n_slots / kBucket;
   ix->lg_buckets = 0;
@@ -368,6 +453,35 @@ int aibx_index_evict(aibx_index_t* index, const uint64_t* d_keys, int64_t n, uin
   if (!aligned(d_keys, 8) || !aligned(d_values_out, 8) || !aligned(d_counters2, 8)) return AIBX_ERR_ALIGN;
   index_evict_kernel<<<pass_grid((u64)n), kIndexThreads, 0, as_stream(stream)>>>(table_of(index), d_keys, n,
                                                                                   d_values_out, d_counters2);
+  return launch_status();
+}
+
+int aibx_index_touch(aibx_index_t* index, const uint64_t* d_keys, int64_t n, uint32_t epoch, void* stream) {
+  if (!index || n < 0 || epoch > kEpochMask) return AIBX_ERR_INVALID_ARG;
+  if (n == 0) return AIBX_OK;
+  if (!d_keys) return AIBX_ERR_INVALID_ARG;
+  if (!aligned(d_keys, 8)) return AIBX_ERR_ALIGN;
+  index_touch_kernel<<<pass_grid((u64)n), kIndexThreads, 0, as_stream(stream)>>>(table_of(index), d_keys, n, epoch);
+  return launch_status();
+}
+
+int aibx_index_age(aibx_index_t* index, void* stream) {
+  if (!index) return AIBX_ERR_INVALID_ARG;
+  index_age_kernel<<<pass_grid(index->n_slots), kIndexThreads, 0, as_stream(stream)>>>(index->usage, index->n_slots);
+  return launch_status();
+}
+
+int aibx_index_select_victims(const aibx_index_t* index, uint32_t protect_count, uint32_t before_epoch,
+                              uint64_t* d_keys_out, uint64_t* d_values_out, uint64_t capacity,
+                              uint64_t* d_n_out, void* stream) {
+  if (!index || !d_n_out) return AIBX_ERR_INVALID_ARG;
+  if (capacity && (!d_keys_out || !d_values_out)) return AIBX_ERR_INVALID_ARG;
+  if (!aligned(d_keys_out, 8) || !aligned(d_values_out, 8) || !aligned(d_n_out, 8)) return AIBX_ERR_ALIGN;
+  hipStream_t st = as_stream(stream);
+  zero_word_kernel<<<1, 1, 0, st>>>(d_n_out);
+  index_victims_kernel<<<pass_grid(index->n_slots), kIndexThreads, 0, st>>>(
+      index->slots, index->usage, index->n_slots, protect_count, before_epoch, d_keys_out, d_values_out, capacity,
+      d_n_out);
   return launch_status();
 }
 

@@ -7,6 +7,7 @@
 
 struct aibx_index {
   aibx::u64* slots;       // device, 2*n_slots words: {key, value} pairs
+  aibx::u32* usage;       // device, n_slots words behind the slots: (touch count << 24) | last epoch
   aibx::u64 n_slots;
   aibx::u64 n_buckets;    // n_slots / 8, power of two
   int lg_buckets;
@@ -23,8 +24,12 @@ constexpr u64 kHomeMul = 0x9E3779B97F4A7C15ull;  // multiplicative (Fibonacci) b
 constexpr int kIndexThreads = 256;
 constexpr int kWavesPerGroup = kIndexThreads / kWave;
 
+constexpr int kSlotBytes = 16, kUsageBytes = 4;  // storage per slot: the slot, then its usage word
+constexpr u32 kEpochMask = 0xFFFFFFu;             // usage word: [31:24] touch count, [23:0] last epoch
+
 struct Table {
   u64* slots;
+  u32* usage;
   u64 bucket_mask;
   int shift;  // 64 - lg(n_buckets); home = (key * kHomeMul) >> shift (0 buckets bits -> 0)
 };
@@ -82,6 +87,7 @@ __device__ __forceinline__ u64 lookup_one(const Table& t, u64 key, bool valid) {
 inline Table table_of(const aibx_index* ix) {
   Table t;
   t.slots = ix->slots;
+  t.usage = ix->usage;
   t.bucket_mask = ix->n_buckets - 1;
   t.shift = 64 - ix->lg_buckets;
   return t;

@@ -132,6 +132,24 @@ class HipIndex:
         order = np.argsort(hk, kind="stable")
         return hk[order], hv[order]
 
+    def touch(self, keys, epoch):
+        k = self._dev(keys)
+        self.a.aibx_index_touch(self.h, k, k.numel(), epoch)
+
+    def age(self):
+        self.a.aibx_index_age(self.h)
+
+    def select_victims(self, protect_count, before_epoch):
+        cap = max(self.count(), 1)
+        k = self.t.empty(cap, dtype=self.t.int64, device="cuda")
+        v = self.t.empty_like(k)
+        n = self.t.empty(1, dtype=self.t.int64, device="cuda")
+        self.a.aibx_index_select_victims(self.h, protect_count, before_epoch, k, v, cap, n)
+        m = int(n.item())
+        hk, hv = self._host_u64(k)[:m], self._host_u64(v)[:m]
+        order = np.argsort(hk, kind="stable")
+        return hk[order], hv[order]
+
     def match(self, hashes, blk_off):
         h = self._dev(hashes)
         bo = self._dev(blk_off, np.int64)

@@ -39,8 +39,8 @@ def test_version_and_strerror(lib):
 
 def test_storage_bytes_rules(lib):
     out = C.c_size_t()
-    assert lib.aibx_index_storage_bytes(1 << 20, C.byref(out)) == 0 and out.value == 16 << 20
-    assert lib.aibx_index_storage_bytes(8, C.byref(out)) == 0 and out.value == 128
+    assert lib.aibx_index_storage_bytes(1 << 20, C.byref(out)) == 0 and out.value == 20 << 20
+    assert lib.aibx_index_storage_bytes(8, C.byref(out)) == 0 and out.value == 160
     for bad in (0, 4, 12, 1000, (1 << 20) + 8, 1 << 40):
         assert lib.aibx_index_storage_bytes(bad, C.byref(out)) == -3
     assert lib.aibx_index_storage_bytes(64, None) == -1
@@ -67,6 +67,9 @@ def test_argument_errors_are_raised_before_any_launch(lib):
     assert lib.aibx_index_evict(None, fake, 1, None, None, None) == -1
     assert lib.aibx_prefix_match(None, fake, fake, 1, 1, None, fake, None) == -1
     assert lib.aibx_index_destroy(None) == 0
+    assert lib.aibx_index_touch(None, fake, 1, 0, None) == -1
+    assert lib.aibx_index_age(None, None) == -1
+    assert lib.aibx_index_select_victims(None, 2, 5, fake, fake, 1, fake, None) == -1
     assert lib.aibx_hash_match(None, fake, fake, fake, 1, 1, 16, 0, fake, fake, fake, None) == -1
     # routing
     assert lib.aibx_route(fake, fake, 1, 1, 0, fake, 1, 2, fake, fake, None) == -1

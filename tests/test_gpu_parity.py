@@ -264,6 +264,64 @@ def test_match_edge_cases():
     assert gm[4] >= 130
 
 
+# ---- usage tracking and victim selection ------------------------------------------------------------
+@pytest.mark.parametrize("n_slots,seed", [(64, 0), (1024, 0), (1024, 1), (1 << 16, 0)])
+def test_eviction_policy_random_ops_against_oracle(n_slots, seed):
+    rng = np.random.default_rng(n_slots + seed)
+    gi, oi = HipIndex(n_slots), oracle.Index(n_slots)
+    universe = np.unique(rng.integers(1, 2**63, size=2 * n_slots, dtype=np.uint64))
+    for step in range(80):
+        op = int(rng.integers(0, 6))
+        m = int(rng.integers(0, max(2, n_slots // 3)))
+        if op == 0:
+            k = rng.choice(universe, size=m, replace=False)
+            if gi.count() + m > n_slots:
+                continue
+            v = rng.integers(0, 2**40, size=m, dtype=np.uint64)
+            gi.insert(k, v)
+            oi.insert(k, v)
+        elif op == 1:
+            k = rng.choice(universe, size=m, replace=False)
+            assert np.array_equal(gi.evict(k), oi.evict(k))
+        elif op == 2 or op == 3:
+            k = rng.choice(universe, size=3 * m, replace=True)       # duplicates: touched several times
+            e = int(rng.integers(0, 40))
+            gi.touch(k, e)
+            oi.touch(k, e)
+        elif op == 4 and step % 5 == 0:
+            gi.age()
+            oi.age()
+        pc, be = int(rng.integers(0, 6)), int(rng.integers(0, 45))
+        gk, gv = gi.select_victims(pc, be)
+        ok, ov = oi.select_victims(pc, be)
+        assert np.array_equal(gk, ok) and np.array_equal(gv, ov), (step, op)
+    # saturation of the touch count
+    k = universe[:1]
+    for ix in (gi, oi):
+        ix.insert(k, k)
+        ix.touch(np.repeat(k, 700), 1)
+    assert np.array_equal(gi.select_victims(255, 50)[0], oi.select_victims(255, 50)[0])
+    assert np.array_equal(gi.select_victims(256, 50)[0], oi.select_victims(256, 50)[0])
+
+
+def test_scan_does_not_push_out_reused_blocks_full_flow():
+    """Config-2-shaped traffic: shared prefixes are touched by every request of their group each
+    epoch, unique tails once; the victims must be exactly the old unique tails."""
+    wl = make_workload(2, "small")
+    h = oracle.block_hash(wl.tokens, wl.tok_off, wl.blk_off, wl.block_size, 0)
+    gi, oi = HipIndex(1 << 14), oracle.Index(1 << 14)
+    uniq = np.unique(h)
+    for ix in (gi, oi):
+        ix.insert(uniq, uniq >> np.uint64(5))
+        for r in range(wl.n_req):                       # request r arrives in epoch r + 1
+            ix.touch(h[wl.blk_off[r]:wl.blk_off[r + 1]], r + 1)
+    gk, gv = gi.select_victims(2, wl.n_req // 2 + 1)
+    ok, ov = oi.select_victims(2, wl.n_req // 2 + 1)
+    assert np.array_equal(gk, ok) and np.array_equal(gv, ov)
+    shared = {int(x) for r in range(wl.n_req) for x in h[wl.blk_off[r]:wl.blk_off[r] + 2048 // wl.block_size]}
+    assert len(ok) > 0 and not (set(int(x) for x in ok) & shared)
+
+
 # ---- hash + match in one launch -------------------------------------------------------------------
 @pytest.mark.parametrize("B,n_req", [(16, 37), (32, 21), (64, 19), (16, 5000), (64, 4500), (24, 11)])
 def test_hash_match_equals_hash_then_match(B, n_req):
