@@ -334,6 +334,19 @@ def survey_config(torch, aibx, cfg, layout=None):
             ms_r, _ = time_calls(torch, mix_round, 20)
             out["mix_1_1_4_round_us"] = ms_r * 1e3
             out["mix_1_1_4_Mops_per_s"] = (2 * q + n_probe) / ms_r / 1e3
+    # eviction policy: touch the batch's blocks, then one victim scan over the whole table
+    ms_t, _ = time_calls(torch, lambda: aibx.aibx_index_touch(ix, h, N, 5), 10)
+    cap = wl.n_slots
+    vk = torch.empty(cap, dtype=torch.int64, device="cuda")
+    vv = torch.empty(cap, dtype=torch.int64, device="cuda")
+    vn = torch.zeros(1, dtype=torch.int64, device="cuda")
+    ms_v, _ = time_calls(torch, lambda: aibx.aibx_index_select_victims(ix, 2, 3, vk, vv, cap, vn), 10)
+    n_vict = int(vn.item())
+    table_bytes = wl.n_slots * 20
+    out["eviction_policy"] = {"touch_Mkeys_per_s": N / ms_t / 1e3, "victim_scan_us": ms_v * 1e3,
+                              "victims": n_vict, "victim_scan_GBps": (table_bytes + 16 * n_vict) / ms_v / 1e6,
+                              "victim_scan_frac_of_hbm_peak": (table_bytes + 16 * n_vict) / ms_v / 1e6 / HBM_PEAK_GBPS}
+    del vk, vv
     # scaled batch
     tok, to, bo = make_scaled_tokens(cfg, 4 << 20)
     Ns, Rs = int(bo[-1]), len(bo) - 1
@@ -348,6 +361,13 @@ def survey_config(torch, aibx, cfg, layout=None):
     out["scaled"] = {"requests": Rs, "blocks": Ns, "hash_ms": ms_h, "match_ms": ms_m, "blocks_per_s": rate,
                      "roofline_frac": rate * per / 1e9 / HBM_PEAK_GBPS, "bytes_per_block": per,
                      "index_slots": wl.n_slots, "load_factor": wl.load_factor}
+    # routing decision on the scaled batch: values read as pod sets (low 8 bits), 8 pods
+    pod_sets = torch.where(v == -1, v, v & 0xFF)
+    load = torch.zeros(8, dtype=torch.int32, device="cuda")
+    pod = torch.empty(Rs, dtype=torch.int32, device="cuda")
+    hit = torch.empty(Rs, dtype=torch.int32, device="cuda")
+    ms_r, _ = time_calls(torch, lambda: aibx.aibx_route(pod_sets, d_bo, Rs, Ns, 8, load, 1, 2, pod, hit), 10)
+    out["route"] = {"requests": Rs, "us": ms_r * 1e3, "Mrequests_per_s": Rs / ms_r / 1e3}
     aibx.aibx_index_destroy(ix)
     return out
 

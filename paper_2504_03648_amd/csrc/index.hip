@@ -291,40 +291,6 @@ __global__ __launch_bounds__(kIndexThreads) void index_age_kernel(u32* usage, u6
   }
 }
 
-// victims: streams over the table and emits every live key whose touch count is below
-// `protect_count` and whose last epoch is before `before_epoch`; positions come from one atomic
-// per wavefront.
-__global__ __launch_bounds__(kIndexThreads) void index_victims_kernel(const u64* slots, const u32* usage,
-                                                                     u64 n_slots, u32 protect_count,
-                                                                     u32 before_epoch, u64* keys_out,
-                                                                     u64* values_out, u64 capacity, u64* n_out) {
-  const int lane = threadIdx.x & (kWave - 1);
-  const u64 stride = (u64)gridDim.x * kIndexThreads;
-  for (u64 i0 = (u64)blockIdx.x * kIndexThreads + (threadIdx.x - lane); i0 < n_slots; i0 += stride) {
-    const u64 i = i0 + lane;
-    u64 k = kEmpty, v = 0;
-    u32 w = ~0u;
-    if (i < n_slots) {
-      k = slots[2 * i];
-      v = slots[2 * i + 1];
-      w = usage[i];
-    }
-    const bool cold = k != kEmpty && k != kTomb && (w >> 24) < protect_count && (w & kEpochMask) < before_epoch;
-    const u64 mask = __ballot(cold);
-    if (mask == 0) continue;
-    u64 start = 0;
-    if (lane == 0) start = atomicAdd((unsigned long long*)n_out, (unsigned long long)__popcll(mask));
-    start = shfl64(start, 0);
-    if (cold) {
-      const u64 pos = start + __popcll(mask & ((1ull << lane) - 1ull));
-      if (pos < capacity) {
-        keys_out[pos] = k;
-        values_out[pos] = v;
-      }
-    }
-  }
-}
-
 // ---- whole-table passes ------------------------------------------------------------------------
 __global__ __launch_bounds__(kIndexThreads) void fill_zero_kernel(uint4* p, u64 n_vec) {
   for (u64 i = (u64)blockIdx.x * kIndexThreads + threadIdx.x; i < n_vec; i += (u64)gridDim.x * kIndexThreads)
@@ -339,36 +305,69 @@ __global__ __launch_bounds__(kIndexThreads) void index_count_kernel(const u64* s
     const u64 k = slots[2 * i];
     mine += (k != kEmpty && k != kTomb);
   }
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) mine += __shfl_xor(mine, m);
-  if ((threadIdx.x & (kWave - 1)) == 0 && mine) atomicAdd((unsigned long long*)live_out, (unsigned long long)mine);
+  const u32 total = group_sum(mine);
+  if (threadIdx.x == 0 && total) atomicAdd((unsigned long long*)live_out, (unsigned long long)total);
 }
 
-__global__ __launch_bounds__(kIndexThreads) void index_dump_kernel(const u64* slots, u64 n_slots, u64* keys_out,
-                                                                  u64* values_out, u64 capacity, u64* n_out) {
-  const int lane = threadIdx.x & (kWave - 1);
-  const u64 stride = (u64)gridDim.x * kIndexThreads;
-  // trip count is the same for all lanes of a wavefront (the ballot needs them all)
-  for (u64 i0 = (u64)blockIdx.x * kIndexThreads + (threadIdx.x - lane); i0 < n_slots; i0 += stride) {
-    const u64 i = i0 + lane;
+// Dump and victim selection: emit the (key, value) pairs of the slots that pass a test, in no
+// particular order. Every workgroup owns one contiguous stretch of the table and goes over it
+// twice: first it counts its matches and reserves that many output positions with ONE atomic (an
+// atomic per wavefront on the shared counter serialises at ~13 ns each and made a scan of a
+// 16 M-slot table take 3 ms), then it re-reads the stretch - mostly from cache - and writes.
+struct EmitTest {
+  bool victims;        // false: every live key; true: live, count < protect_count, last < before_epoch
+  u32 protect_count, before_epoch;
+};
+
+__device__ __forceinline__ bool emit_passes(const EmitTest& e, u64 key, u32 usage) {
+  const bool live = key != kEmpty && key != kTomb;
+  if (!e.victims) return live;
+  return live && (usage >> 24) < e.protect_count && (usage & kEpochMask) < e.before_epoch;
+}
+
+__global__ __launch_bounds__(kIndexThreads) void index_emit_kernel(const u64* slots, const u32* usage, u64 n_slots,
+                                                                  EmitTest test, u64* keys_out, u64* values_out,
+                                                                  u64 capacity, u64* n_out) {
+  __shared__ u64 lds_base;
+  __shared__ u32 lds_wave[kWavesPerGroup];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  u64 chunk = (n_slots + gridDim.x - 1) / gridDim.x;
+  chunk = (chunk + kIndexThreads - 1) / kIndexThreads * kIndexThreads;
+  const u64 begin = (u64)blockIdx.x * chunk;
+  const u64 end = begin + chunk < n_slots ? begin + chunk : n_slots;
+  u32 mine = 0;
+  for (u64 i = begin + threadIdx.x; i < end; i += kIndexThreads)
+    mine += emit_passes(test, slots[2 * i], test.victims ? usage[i] : 0u);
+  const u32 total = group_sum(mine);  // valid in thread 0
+  if (threadIdx.x == 0) lds_base = total ? atomicAdd((unsigned long long*)n_out, (unsigned long long)total) : 0ull;
+  __syncthreads();
+  u64 pos0 = lds_base;  // next free output position of this workgroup
+  for (u64 tile = begin; tile < end; tile += kIndexThreads) {  // same trip count for every thread
+    const u64 i = tile + threadIdx.x;
     u64 k = kEmpty, v = 0;
-    if (i < n_slots) {
+    bool pass = false;
+    if (i < end) {
       k = slots[2 * i];
-      v = slots[2 * i + 1];
+      pass = emit_passes(test, k, test.victims ? usage[i] : 0u);
+      if (pass) v = slots[2 * i + 1];
     }
-    const bool live = k != kEmpty && k != kTomb;
-    const u64 mask = __ballot(live);
-    if (mask == 0) continue;
-    u64 start = 0;
-    if (lane == 0) start = atomicAdd((unsigned long long*)n_out, (unsigned long long)__popcll(mask));
-    start = shfl64(start, 0);
-    if (live) {
-      const u64 pos = start + __popcll(mask & ((1ull << lane) - 1ull));
+    const u64 mask = __ballot(pass);
+    if (lane == 0) lds_wave[wave] = (u32)__popcll(mask);
+    __syncthreads();
+    u32 before = 0, all = 0;
+    for (int w = 0; w < kWavesPerGroup; ++w) {
+      before += w < wave ? lds_wave[w] : 0u;
+      all += lds_wave[w];
+    }
+    if (pass) {
+      const u64 pos = pos0 + before + __popcll(mask & ((1ull << lane) - 1ull));
       if (pos < capacity) {
         keys_out[pos] = k;
         values_out[pos] = v;
       }
     }
+    pos0 += all;
+    __syncthreads();  // lds_wave is rewritten by the next tile
   }
 }
 
@@ -479,9 +478,9 @@ int aibx_index_select_victims(const aibx_index_t* index, uint32_t protect_count,
   if (!aligned(d_keys_out, 8) || !aligned(d_values_out, 8) || !aligned(d_n_out, 8)) return AIBX_ERR_ALIGN;
   hipStream_t st = as_stream(stream);
   zero_word_kernel<<<1, 1, 0, st>>>(d_n_out);
-  index_victims_kernel<<<pass_grid(index->n_slots), kIndexThreads, 0, st>>>(
-      index->slots, index->usage, index->n_slots, protect_count, before_epoch, d_keys_out, d_values_out, capacity,
-      d_n_out);
+  index_emit_kernel<<<pass_grid(index->n_slots), kIndexThreads, 0, st>>>(
+      index->slots, index->usage, index->n_slots, EmitTest{true, protect_count, before_epoch}, d_keys_out,
+      d_values_out, capacity, d_n_out);
   return launch_status();
 }
 
@@ -501,8 +500,9 @@ int aibx_index_dump(const aibx_index_t* index, uint64_t* d_keys_out, uint64_t* d
   if (!aligned(d_keys_out, 8) || !aligned(d_values_out, 8) || !aligned(d_n_out, 8)) return AIBX_ERR_ALIGN;
   hipStream_t st = as_stream(stream);
   zero_word_kernel<<<1, 1, 0, st>>>(d_n_out);
-  index_dump_kernel<<<pass_grid(index->n_slots), kIndexThreads, 0, st>>>(index->slots, index->n_slots, d_keys_out,
-                                                                         d_values_out, capacity, d_n_out);
+  index_emit_kernel<<<pass_grid(index->n_slots), kIndexThreads, 0, st>>>(
+      index->slots, index->usage, index->n_slots, EmitTest{false, 0, 0}, d_keys_out, d_values_out, capacity,
+      d_n_out);
   return launch_status();
 }
 
