@@ -2,9 +2,10 @@
 // routing, Section 3.2.2, and its cross-request KV reuse, Section 3.2.5). The definition is in
 // aibx.h; this file evaluates it on the GPU.
 //
-// Layout of the work: one workgroup of 4 wavefronts (or, for large batches, 1) per request. A wavefront takes a
-// tile of 1024 consecutive tokens (64 coalesced tokens per load, 16 loads in flight), so a lane
-// always sees the same position-in-block and folds its position constant once. The per-block sums
+// Layout of the work: one workgroup of 4 wavefronts (or, for large batches, 1) per request. A
+// wavefront takes a tile of 1024 consecutive tokens (64 coalesced tokens per load, 16 loads in
+// flight), so a lane always sees the same position-in-block and folds its position constant once
+// (request starts are only 4-byte aligned, so wider loads would need peeling). The per-block sums
 // are formed by a transposing butterfly across the lanes that share a block (DPP lane patterns
 // inside a row of 16 lanes, bpermute only across rows), the block digests are scanned with the
 // chain's affine step (s -> K2*s + d) by DPP row shifts inside each row and a 4-step scalar chain
@@ -51,6 +52,13 @@ __device__ __forceinline__ u64 shfl_xor64(u64 v, int mask) {
   u32 lo = (u32)v, hi = (u32)(v >> 32);
   lo = __shfl_xor(lo, mask);
   hi = __shfl_xor(hi, mask);
+  return ((u64)hi << 32) | lo;
+}
+
+__device__ __forceinline__ u64 shfl64(u64 v, int src) {
+  u32 lo = (u32)v, hi = (u32)(v >> 32);
+  lo = __shfl(lo, src);
+  hi = __shfl(hi, src);
   return ((u64)hi << 32) | lo;
 }
 

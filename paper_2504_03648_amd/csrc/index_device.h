@@ -44,13 +44,6 @@ __device__ __forceinline__ u64 home_bucket(const Table& t, u64 key) {
 // An odd step modulo a power of two visits every bucket once.
 __device__ __forceinline__ u64 probe_step(u64 key) { return ((key * kHomeMul) >> 7) | 1ull; }
 
-__device__ __forceinline__ u64 shfl64(u64 v, int src) {
-  u32 lo = (u32)v, hi = (u32)(v >> 32);
-  lo = __shfl(lo, src);
-  hi = __shfl(hi, src);
-  return ((u64)hi << 32) | lo;
-}
-
 typedef __attribute__((ext_vector_type(2))) u64 slot_t;  // .x = key, .y = value
 
 // ---- lookup ------------------------------------------------------------------------------------

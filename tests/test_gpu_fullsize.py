@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 import oracle
-from backends import HipIndex
+from backends import HipIndex, hip_hash_match
 from workloads import Geometry, fill_pool_torch, filler_keys, make_workload
 
 pytestmark = pytest.mark.gpu
@@ -47,6 +47,23 @@ def test_index_and_match_full_size(cfg):
     ok, ovv = oi.dump()
     assert np.array_equal(gk, ok) and np.array_equal(gvv, ovv)
     assert np.array_equal(gi.counters_evict, oi.counters_evict)
+    # the one-launch path on the same index state
+    fh, fv, fm = hip_hash_match(gi, wl.tokens, wl.tok_off, wl.blk_off, wl.block_size, 0)
+    assert np.array_equal(fh, h) and np.array_equal(fv, ov) and np.array_equal(fm, om)
+    # eviction policy at the full table size: every request touches its blocks in its own epoch
+    for r in range(0, wl.n_req, max(1, wl.n_req // 64)):
+        blk = h[wl.blk_off[r]:wl.blk_off[r + 1]]
+        gi.touch(blk, r + 1)
+        oi.touch(blk, r + 1)
+    for pc, be in [(2, wl.n_req // 2 + 1), (1, 1)]:
+        gk2, gv2 = gi.select_victims(pc, be)
+        ok2, ov2 = oi.select_victims(pc, be)
+        assert np.array_equal(gk2, ok2) and np.array_equal(gv2, ov2)
+    gi.age()
+    oi.age()
+    gk2, _ = gi.select_victims(1, 1 << 20)
+    ok2, _ = oi.select_victims(1, 1 << 20)
+    assert np.array_equal(gk2, ok2)
     del gi
     _free()
 
