@@ -287,6 +287,33 @@ def survey_config(torch, aibx, cfg, layout=None):
         torch.cuda.synchronize()
         walls.append(max(e0.elapsed_time(e1), e0.elapsed_time(e2)))
     out["two_stream_gather_scatter_GBps"] = 2 * traffic / sorted(walls)[len(walls) // 2] / 1e6
+    # host tier: offload / onload of 1024 blocks through pinned host memory, 64-block chunks
+    nh = min(1024, n)
+    chunk = 64
+    h_buf = torch.empty(nh * g.blk_bytes, dtype=torch.uint8).pin_memory()
+    st2 = staging[: 2 * chunk * g.blk_bytes]
+
+    def tier(fn):
+        ts = []
+        for _ in range(3):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            fn(desc, pa, nh, st2, chunk, g.blk_bytes, h_buf, g.blk_bytes, None, s1, s2)
+            s1.synchronize()
+            s2.synchronize()
+            ts.append(time.perf_counter() - t0)
+        return sorted(ts)[1]
+    t_off, t_on = tier(aibx.aibx_kv_offload), tier(aibx.aibx_kv_onload)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    h_buf.copy_(staging[: h_buf.numel()], non_blocking=True)
+    torch.cuda.synchronize()
+    t_plain = time.perf_counter() - t0
+    out["host_tier"] = {"blocks": nh, "chunk_blocks": chunk, "offload_GBps": nh * g.blk_bytes / t_off / 1e9,
+                        "onload_GBps": nh * g.blk_bytes / t_on / 1e9,
+                        "plain_d2h_copy_GBps": nh * g.blk_bytes / t_plain / 1e9,
+                        "offload_vs_plain_transfer": t_plain / t_off}
+    del h_buf
     del pool, staging
     torch.cuda.empty_cache()
     # index + hash at native size

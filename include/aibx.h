@@ -15,6 +15,7 @@
  *   aibx_index_touch / _age / _select_victims   scan-resistant victim selection (Section 3.2.5)
  *   aibx_kv_gather     paged KV pool -> contiguous staging (offload)     (Section 3.2.5)
  *   aibx_kv_scatter    contiguous staging -> paged KV pool (onload)      (Section 3.2.5)
+ *   aibx_kv_offload / aibx_kv_onload   the same through to pinned host memory, pipelined
  *
  * The paper prints no hash function, index layout or copy layout; the rules stated below are
  * this library's own and are what its results are checked against.
@@ -254,6 +255,33 @@ int aibx_kv_gather(const aibx_pool_desc* pool, const int32_t* d_page_ids,
 int aibx_kv_scatter(const aibx_pool_desc* pool, const int32_t* d_page_ids,
                     const int32_t* d_slot_ids, int64_t n, const void* d_staging,
                     uint64_t staging_block_stride, uint64_t* d_bad_page_counter, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Host-tier leg: paged pool <-> pinned host memory through a two-part staging buffer in HBM.
+ * (Section 3.2.5: the cache pool is DRAM-based and exchanges KV with the colocated engine through
+ * host memory.) Offload: chunks of `chunk_blocks` pages are gathered into the two halves of
+ * d_staging in turn on stream_copy, and each gathered chunk is sent to host memory on stream_xfer
+ * while the next one is gathered. Onload is the mirror image: chunk k travels host -> staging on
+ * stream_xfer while chunk k-1 is scattered on stream_copy.
+ *   Entry i moves page d_page_ids[i] <-> host block i at h_buf + i*host_block_stride (the n_seg
+ *   segments back to back, as in a staging block). Holes and out-of-range pages are skipped as in
+ *   aibx_kv_gather/_scatter; on offload the host block of a skipped entry receives unspecified bytes.
+ *   d_staging: 2*chunk_blocks*staging_block_stride bytes of device memory, 16-byte aligned.
+ *   h_dst / h_src: HOST memory, pinned (page-locked) for the transfer to be asynchronous, 16-byte
+ *   aligned; host_block_stride multiple of 16, >= n_seg*seg_bytes. stream_copy != stream_xfer.
+ * The calls only enqueue. When aibx_kv_offload returns, everything is ordered before later work on
+ * stream_copy (it waits for the transfers); when aibx_kv_onload returns, the last scatter is on
+ * stream_copy and stream_xfer has been made to start after the work already queued on stream_copy.
+ * The staging buffer and the host buffer must stay untouched until stream_copy has drained.
+ * Errors: INVALID_ARG, ALIGN, HIP. */
+int aibx_kv_offload(const aibx_pool_desc* pool, const int32_t* d_page_ids, int64_t n, void* d_staging,
+                    int64_t chunk_blocks, uint64_t staging_block_stride, void* h_dst,
+                    uint64_t host_block_stride, uint64_t* d_bad_page_counter, void* stream_copy,
+                    void* stream_xfer);
+int aibx_kv_onload(const aibx_pool_desc* pool, const int32_t* d_page_ids, int64_t n, void* d_staging,
+                   int64_t chunk_blocks, uint64_t staging_block_stride, const void* h_src,
+                   uint64_t host_block_stride, uint64_t* d_bad_page_counter, void* stream_copy,
+                   void* stream_xfer);
 
 #ifdef __cplusplus
 }

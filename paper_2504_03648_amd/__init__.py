@@ -8,4 +8,4 @@ from .binding import (AibxError, PoolDesc, AIBX_NO_VALUE, aibx_version, aibx_has
                       aibx_index_count, aibx_index_dump, aibx_index_touch, aibx_index_age,
                       aibx_index_select_victims, aibx_prefix_match, aibx_hash_match, aibx_route,
                       make_pool_desc,
-                      aibx_kv_gather, aibx_kv_scatter)
+                      aibx_kv_gather, aibx_kv_scatter, aibx_kv_offload, aibx_kv_onload)

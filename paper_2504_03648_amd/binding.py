@@ -17,7 +17,7 @@ EXPORTS = [
     "aibx_block_hash", "aibx_index_storage_bytes", "aibx_index_create", "aibx_index_destroy",
     "aibx_index_clear", "aibx_index_insert", "aibx_index_evict", "aibx_index_count",
     "aibx_index_dump", "aibx_index_touch", "aibx_index_age", "aibx_index_select_victims",
-    "aibx_prefix_match", "aibx_hash_match", "aibx_route", "aibx_kv_gather", "aibx_kv_scatter",
+    "aibx_prefix_match", "aibx_hash_match", "aibx_route", "aibx_kv_gather", "aibx_kv_scatter", "aibx_kv_offload", "aibx_kv_onload",
 ]
 
 
@@ -73,6 +73,8 @@ def load(build_if_missing: bool = True):
     lib.aibx_hash_match.argtypes = [vp, vp, vp, vp, i32, i64, i32, u64, vp, vp, vp, vp]
     for f in (lib.aibx_kv_gather, lib.aibx_kv_scatter):
         f.argtypes = [C.POINTER(PoolDesc), vp, vp, i64, vp, u64, vp, vp]
+    for f in (lib.aibx_kv_offload, lib.aibx_kv_onload):
+        f.argtypes = [C.POINTER(PoolDesc), vp, i64, vp, i64, u64, vp, u64, vp, vp, vp]
     for name in EXPORTS[4:]:
         getattr(lib, name).restype = C.c_int
     _lib = lib
@@ -220,3 +222,27 @@ def aibx_kv_scatter(pool: PoolDesc, d_page_ids, d_slot_ids, n, d_staging, stagin
     _check("aibx_kv_scatter", load().aibx_kv_scatter(
         C.byref(pool), _p(d_page_ids, torch.int32), _p(d_slot_ids, torch.int32), int(n),
         _p(d_staging), int(staging_block_stride), _p(d_bad_page_counter, U64), _s(stream)))
+
+
+def _host_ptr(t):
+    if not isinstance(t, torch.Tensor) or t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous host tensor")
+    if not t.is_pinned():
+        raise ValueError("the host buffer must be pinned memory (torch.empty(..., pin_memory=True))")
+    return C.c_void_p(t.data_ptr())
+
+
+def aibx_kv_offload(pool: PoolDesc, d_page_ids, n, d_staging, chunk_blocks, staging_block_stride, h_dst,
+                    host_block_stride, d_bad_page_counter, stream_copy, stream_xfer):
+    _check("aibx_kv_offload", load().aibx_kv_offload(
+        C.byref(pool), _p(d_page_ids, torch.int32), int(n), _p(d_staging), int(chunk_blocks),
+        int(staging_block_stride), _host_ptr(h_dst), int(host_block_stride), _p(d_bad_page_counter, U64),
+        _s(stream_copy), _s(stream_xfer)))
+
+
+def aibx_kv_onload(pool: PoolDesc, d_page_ids, n, d_staging, chunk_blocks, staging_block_stride, h_src,
+                   host_block_stride, d_bad_page_counter, stream_copy, stream_xfer):
+    _check("aibx_kv_onload", load().aibx_kv_onload(
+        C.byref(pool), _p(d_page_ids, torch.int32), int(n), _p(d_staging), int(chunk_blocks),
+        int(staging_block_stride), _host_ptr(h_src), int(host_block_stride), _p(d_bad_page_counter, U64),
+        _s(stream_copy), _s(stream_xfer)))

@@ -437,6 +437,45 @@ def test_gather_then_scatter_is_identity_on_the_pool():
     assert hb.t.equal(hb.pool, keep)
 
 
+# ---- host tier ----------------------------------------------------------------------------------
+@pytest.mark.parametrize("n_seg,seg_bytes,n,chunk,pad", [(6, 4096, 77, 16, 0), (1, 65536, 40, 64, 0),
+                                                         (64, 32768, 50, 7, 0), (3, 48, 33, 4, 32)])
+def test_offload_to_host_and_onload_back(n_seg, seg_bytes, n, chunk, pad):
+    import torch
+    import paper_2504_03648_amd as aibx
+    g = Geometry(n_seg, seg_bytes, 200)
+    rng = np.random.default_rng(n_seg + n)
+    host_pool = rng.integers(0, 256, size=g.pool_bytes, dtype=np.uint8)
+    hb = HipBackend()
+    hb.pool_create(g, None, None, host_bytes=host_pool.copy())
+    ids = rng.permutation(200)[:n].astype(np.int32)
+    ids[3], ids[5] = -1, 200                               # a hole and a bad page
+    d_ids = torch.from_numpy(ids).cuda()
+    st_stride, h_stride = g.blk_bytes + pad, g.blk_bytes + 2 * pad
+    staging = torch.zeros(2 * chunk * st_stride, dtype=torch.uint8, device="cuda")
+    h_buf = torch.full((n * h_stride,), 0x3C, dtype=torch.uint8).pin_memory()
+    bad = torch.zeros(1, dtype=torch.int64, device="cuda")
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    aibx.aibx_kv_offload(hb.desc, d_ids, n, staging, chunk, st_stride, h_buf, h_stride, bad, s1, s2)
+    s1.synchronize()
+    want = np.full(n * h_stride, 0x3C, dtype=np.uint8)
+    assert oracle.kv_gather(host_pool, g.as_tuple(), ids, None, want, h_stride) == 1
+    got = h_buf.numpy().reshape(n, h_stride)
+    moved = np.ones(n, dtype=bool)
+    moved[[3, 5]] = False
+    assert np.array_equal(got[moved][:, : g.blk_bytes], want.reshape(n, h_stride)[moved][:, : g.blk_bytes])
+    assert np.all(got[:, g.blk_bytes:] == 0x3C)            # padding between host blocks untouched
+    assert int(bad.item()) == 1
+    # wipe the moved pages, bring them back from the host copy
+    hb.fill_pages(ids[moved], 0xA5)
+    aibx.aibx_kv_onload(hb.desc, d_ids, n, staging, chunk, st_stride, h_buf, h_stride, bad, s1, s2)
+    s1.synchronize()
+    s2.synchronize()
+    assert np.array_equal(hb.pool.cpu().numpy(), host_pool)
+    assert int(bad.item()) == 2
+
+
 # ---- whole flows on the small configs ----------------------------------------------------------
 @pytest.mark.parametrize("cfg", [1, 3, 4])
 def test_flow_match_roundtrip_small(cfg):
