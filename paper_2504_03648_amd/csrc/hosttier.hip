@@ -30,6 +30,14 @@ struct Events {
     if (e_ != hipSuccess) return hip_failed(e_);  \
   } while (0)
 
+// One chunk between staging and host: a linear copy when both sides are densely packed, a pitched
+// copy otherwise.
+hipError_t copy_chunk(void* dst, u64 dst_stride, const void* src, u64 src_stride, u64 blk_bytes, int64_t m,
+                      hipMemcpyKind kind, hipStream_t st) {
+  if (dst_stride == blk_bytes && src_stride == blk_bytes) return hipMemcpyAsync(dst, src, blk_bytes * (u64)m, kind, st);
+  return hipMemcpy2DAsync(dst, dst_stride, src, src_stride, blk_bytes, (size_t)m, kind, st);
+}
+
 int check_tier_args(const aibx_pool_desc* pool, const int32_t* d_page_ids, int64_t n, void* d_staging,
                     int64_t chunk_blocks, u64 staging_stride, void* h_buf, u64 host_stride, void* s_copy,
                     void* s_xfer) {
@@ -76,8 +84,8 @@ int aibx_kv_offload(const aibx_pool_desc* pool, const int32_t* d_page_ids, int64
     if (erc != AIBX_OK) return erc;
     AIBX_HIP(hipEventRecord(gathered, sc));
     AIBX_HIP(hipStreamWaitEvent(sx, gathered, 0));
-    AIBX_HIP(hipMemcpy2DAsync(static_cast<unsigned char*>(h_dst) + (u64)first * host_block_stride, host_block_stride,
-                              stage, staging_block_stride, blk_bytes, (size_t)m, hipMemcpyDeviceToHost, sx));
+    AIBX_HIP(copy_chunk(static_cast<unsigned char*>(h_dst) + (u64)first * host_block_stride, host_block_stride,
+                        stage, staging_block_stride, blk_bytes, m, hipMemcpyDeviceToHost, sx));
     erc = events.make(&sent[half]);
     if (erc != AIBX_OK) return erc;
     AIBX_HIP(hipEventRecord(sent[half], sx));
@@ -109,9 +117,9 @@ int aibx_kv_onload(const aibx_pool_desc* pool, const int32_t* d_page_ids, int64_
     const int half = (int)(k & 1);
     unsigned char* stage = static_cast<unsigned char*>(d_staging) + (u64)half * (u64)chunk_blocks * staging_block_stride;
     if (scattered[half]) AIBX_HIP(hipStreamWaitEvent(sx, scattered[half], 0));
-    AIBX_HIP(hipMemcpy2DAsync(stage, staging_block_stride,
-                              static_cast<const unsigned char*>(h_src) + (u64)first * host_block_stride, host_block_stride,
-                              blk_bytes, (size_t)m, hipMemcpyHostToDevice, sx));
+    AIBX_HIP(copy_chunk(stage, staging_block_stride,
+                        static_cast<const unsigned char*>(h_src) + (u64)first * host_block_stride, host_block_stride,
+                        blk_bytes, m, hipMemcpyHostToDevice, sx));
     hipEvent_t loaded;
     erc = events.make(&loaded);
     if (erc != AIBX_OK) return erc;
