@@ -293,22 +293,27 @@ def survey_config(torch, aibx, cfg, layout=None):
     h_buf = torch.empty(nh * g.blk_bytes, dtype=torch.uint8).pin_memory()
     st2 = staging[: 2 * chunk * g.blk_bytes]
 
+    h_buf.zero_()                                     # first touch of the pinned pages is not timed
+
     def tier(fn):
         ts = []
-        for _ in range(3):
+        for _ in range(5):
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             fn(desc, pa, nh, st2, chunk, g.blk_bytes, h_buf, g.blk_bytes, None, s1, s2)
             s1.synchronize()
             s2.synchronize()
             ts.append(time.perf_counter() - t0)
-        return sorted(ts)[1]
+        return sorted(ts)[2]
     t_off, t_on = tier(aibx.aibx_kv_offload), tier(aibx.aibx_kv_onload)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    h_buf.copy_(staging[: h_buf.numel()], non_blocking=True)
-    torch.cuda.synchronize()
-    t_plain = time.perf_counter() - t0
+    plain = []
+    for _ in range(3):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        h_buf.copy_(staging[: h_buf.numel()], non_blocking=True)
+        torch.cuda.synchronize()
+        plain.append(time.perf_counter() - t0)
+    t_plain = sorted(plain)[1]
     out["host_tier"] = {"blocks": nh, "chunk_blocks": chunk, "offload_GBps": nh * g.blk_bytes / t_off / 1e9,
                         "onload_GBps": nh * g.blk_bytes / t_on / 1e9,
                         "plain_d2h_copy_GBps": nh * g.blk_bytes / t_plain / 1e9,
