@@ -177,6 +177,22 @@ def time_calls(torch, fn, reps, warm=2):
     return ms[len(ms) // 2], ms[0]
 
 
+def time_calls_cold(torch, fn, reps, flush):
+    """Like time_calls, but a 1 GiB buffer is rewritten before every timed call, so that neither
+    the L2s nor the Infinity Cache hold the call's inputs."""
+    ms = []
+    for _ in range(reps):
+        flush.add_(1)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        torch.cuda.synchronize()
+        ms.append(a.elapsed_time(b))
+    ms.sort()
+    return ms[len(ms) // 2]
+
+
 def scaled_hash_match(torch, aibx, cfg, step, min_blocks):
     """Scaled batch: hash and match >= min_blocks blocks in one launch each, index unchanged."""
     from workloads import make_scaled_tokens
@@ -342,7 +358,16 @@ def survey_config(torch, aibx, cfg, layout=None):
         aibx.aibx_index_insert(ix, fk, fv, n_fill, c[0:3])
     ms_h, _ = time_calls(torch, lambda: aibx.aibx_block_hash(d_tok, d_to, d_bo, R, N, B, 0, h), 20)
     ms_m, _ = time_calls(torch, lambda: aibx.aibx_prefix_match(ix, h, d_bo, R, N, v, m), 20)
-    out["native"] = {"requests": R, "blocks": N, "hash_us": ms_h * 1e3, "match_us": ms_m * 1e3}
+    flush = torch.zeros(1 << 27, dtype=torch.int64, device="cuda")
+    cold_h = time_calls_cold(torch, lambda: aibx.aibx_block_hash(d_tok, d_to, d_bo, R, N, B, 0, h), 7, flush)
+    cold_m = time_calls_cold(torch, lambda: aibx.aibx_prefix_match(ix, h, d_bo, R, N, v, m), 7, flush)
+    cold_f = time_calls_cold(torch, lambda: aibx.aibx_hash_match(ix, d_tok, d_to, d_bo, R, N, B, 0, None, v, m), 7,
+                             flush)
+    ms_f, _ = time_calls(torch, lambda: aibx.aibx_hash_match(ix, d_tok, d_to, d_bo, R, N, B, 0, None, v, m), 20)
+    del flush
+    out["native"] = {"requests": R, "blocks": N, "hash_us": ms_h * 1e3, "match_us": ms_m * 1e3,
+                     "hash_match_one_launch_us": ms_f * 1e3, "cold_cache_hash_us": cold_h * 1e3,
+                     "cold_cache_match_us": cold_m * 1e3, "cold_cache_hash_match_one_launch_us": cold_f * 1e3}
     # update rates: evict then re-insert q filler keys (rounds of the 1:1:4 mix use q = 4096)
     if n_fill >= 1 << 16:
         q = 1 << 16

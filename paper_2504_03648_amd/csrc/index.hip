@@ -4,8 +4,8 @@
 //
 // Behind the slots the storage holds one 32-bit usage word per slot (touch count and last epoch)
 // for the victim selection of the eviction policy.
-// Table: open addressing over buckets of 8 slots; a slot is {u64 key, u64 value}, so a bucket is
-// one 128-byte line. Key 0 = EMPTY, key 2^64-1 = TOMBSTONE. A key lives in the first bucket of
+// Table: open addressing over buckets of 8 slots; a bucket is one 128-byte line holding its 8 keys
+// and then its 8 values. Key 0 = EMPTY, key 2^64-1 = TOMBSTONE. A key lives in the first bucket of
 // its probe sequence (home, home+step, home+2*step, ... mod n_buckets, step odd and key-dependent)
 // that had a free slot when it was inserted.
 // Invariant kept by every kernel: a probe sequence continues past a bucket only if that bucket
@@ -116,14 +116,13 @@ __global__ __launch_bounds__(kIndexThreads) void index_insert_kernel(
   u64 guard = n_buckets > (1ull << 30) ? ~0ull : n_buckets * (n_buckets * kBucket + 1);
   bool fresh = false;  // set after a lost claim
   while (active) {
-    u64* bucket = t.slots + 2 * b * kBucket;
+    u64* bucket = bucket_words(t, b);
     u64 seen[kBucket];
     if (fresh) {
 #pragma unroll
-      for (int j = 0; j < kBucket; ++j) seen[j] = load_key_fresh(bucket + 2 * j);
+      for (int j = 0; j < kBucket; ++j) seen[j] = load_key_fresh(bucket + j);
     } else {
-#pragma unroll
-      for (int j = 0; j < kBucket; ++j) seen[j] = reinterpret_cast<const slot_t*>(bucket)[j].x;
+      load_bucket_keys(bucket, seen);
     }
     int hit = -1, first_free = -1;
     bool any_empty = false;
@@ -134,7 +133,7 @@ __global__ __launch_bounds__(kIndexThreads) void index_insert_kernel(
       any_empty |= seen[j] == kEmpty;
     }
     if (hit >= 0) {  // present: overwrite the value
-      store_value(bucket + 2 * hit + 1, val);
+      store_value(bucket + kBucket + hit, val);
       ++n_upd;
       break;
     }
@@ -155,17 +154,17 @@ __global__ __launch_bounds__(kIndexThreads) void index_insert_kernel(
       ++n_full;  // every slot of the table is taken
       break;
     } else {
-      u64* cslot = t.slots + 2 * (cand_bucket * kBucket + cand_slot);
+      u64* cslot = bucket_words(t, cand_bucket) + cand_slot;  // the candidate's key word
       const u64 old = atomicCAS((unsigned long long*)cslot, (unsigned long long)cand_expected,
                                 (unsigned long long)key);
       if (old == cand_expected) {  // the slot is ours
-        store_value(cslot + 1, val);
+        store_value(cslot + kBucket, val);
         t.usage[cand_bucket * kBucket + cand_slot] = 0;  // a new key starts untouched
         ++n_ins;
         break;
       }
       if (old == key) {  // the same key was stored there a moment ago
-        store_value(cslot + 1, val);
+        store_value(cslot + kBucket, val);
         ++n_upd;
         break;
       }
@@ -210,10 +209,9 @@ __global__ __launch_bounds__(kIndexThreads) void index_evict_kernel(
   const u64 step = probe_step(key);
   u64 b = home_bucket(t, key);
   for (u64 probes = 0; active; ++probes) {
-    u64* bucket = t.slots + 2 * b * kBucket;
+    u64* bucket = bucket_words(t, b);
     u64 seen[kBucket];
-#pragma unroll
-    for (int j = 0; j < kBucket; ++j) seen[j] = reinterpret_cast<const slot_t*>(bucket)[j].x;
+    load_bucket_keys(bucket, seen);
     int hit = -1;
     bool any_empty = false;
 #pragma unroll
@@ -222,10 +220,10 @@ __global__ __launch_bounds__(kIndexThreads) void index_evict_kernel(
       any_empty |= seen[j] == kEmpty;
     }
     if (hit >= 0) {
-      u64* slot = bucket + 2 * hit;
+      u64* slot = bucket + hit;
       const u64 old = atomicCAS((unsigned long long*)slot, (unsigned long long)key,
                                 (unsigned long long)(any_empty ? kEmpty : kTomb));
-      if (old == key) result = slot[1];  // otherwise another entry of this batch removed it first
+      if (old == key) result = slot[kBucket];  // otherwise another entry of this batch removed it first
       break;
     }
     if (any_empty || probes + 1 >= n_buckets) break;
@@ -256,14 +254,14 @@ __global__ __launch_bounds__(kIndexThreads) void index_touch_kernel(Table t, con
     const u64 step = probe_step(key);
     u64 b = home_bucket(t, key);
     for (u64 seen_buckets = 0;; ++seen_buckets) {
-      const slot_t* bucket = reinterpret_cast<const slot_t*>(t.slots + 2 * b * kBucket);
+      u64 k[kBucket];
+      load_bucket_keys(bucket_words(t, b), k);
       int hit = -1;
       bool ends = seen_buckets >= t.bucket_mask;
 #pragma unroll
       for (int j = 0; j < kBucket; ++j) {
-        const u64 k = bucket[j].x;
-        if (k == key) hit = j;
-        ends |= k == kEmpty;
+        if (k[j] == key) hit = j;
+        ends |= k[j] == kEmpty;
       }
       if (hit >= 0) {
         u32* word = t.usage + b * kBucket + hit;
@@ -302,7 +300,7 @@ __global__ void zero_word_kernel(u64* p) { *p = 0; }
 __global__ __launch_bounds__(kIndexThreads) void index_count_kernel(const u64* slots, u64 n_slots, u64* live_out) {
   u32 mine = 0;
   for (u64 i = (u64)blockIdx.x * kIndexThreads + threadIdx.x; i < n_slots; i += (u64)gridDim.x * kIndexThreads) {
-    const u64 k = slots[2 * i];
+    const u64 k = slots[key_word_of_slot(i)];
     mine += (k != kEmpty && k != kTomb);
   }
   const u32 total = group_sum(mine);
@@ -337,7 +335,7 @@ __global__ __launch_bounds__(kIndexThreads) void index_emit_kernel(const u64* sl
   const u64 end = begin + chunk < n_slots ? begin + chunk : n_slots;
   u32 mine = 0;
   for (u64 i = begin + threadIdx.x; i < end; i += kIndexThreads)
-    mine += emit_passes(test, slots[2 * i], test.victims ? usage[i] : 0u);
+    mine += emit_passes(test, slots[key_word_of_slot(i)], test.victims ? usage[i] : 0u);
   const u32 total = group_sum(mine);  // valid in thread 0
   if (threadIdx.x == 0) lds_base = total ? atomicAdd((unsigned long long*)n_out, (unsigned long long)total) : 0ull;
   __syncthreads();
@@ -347,9 +345,9 @@ __global__ __launch_bounds__(kIndexThreads) void index_emit_kernel(const u64* sl
     u64 k = kEmpty, v = 0;
     bool pass = false;
     if (i < end) {
-      k = slots[2 * i];
+      k = slots[key_word_of_slot(i)];
       pass = emit_passes(test, k, test.victims ? usage[i] : 0u);
-      if (pass) v = slots[2 * i + 1];
+      if (pass) v = slots[key_word_of_slot(i) + kBucket];
     }
     const u64 mask = __ballot(pass);
     if (lane == 0) lds_wave[wave] = (u32)__popcll(mask);
