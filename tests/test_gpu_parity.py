@@ -476,6 +476,72 @@ def test_offload_to_host_and_onload_back(n_seg, seg_bytes, n, chunk, pad):
     assert int(bad.item()) == 2
 
 
+# ---- HIP graph capture ----------------------------------------------------------------------------
+def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
+    """Every entry point only launches kernels on the caller's stream (no allocation, no memset), so
+    a sequence of calls can be captured once and replayed. Each replay is checked against the
+    eager results, with eager work and synchronisations between the replays."""
+    import torch
+    import paper_2504_03648_amd as aibx
+    wl = make_workload(2, "small")
+    g = wl.geom
+    d_tok = torch.from_numpy(wl.tokens).cuda()
+    d_to, d_bo = torch.from_numpy(wl.tok_off).cuda(), torch.from_numpy(wl.blk_off).cuda()
+    N, R = wl.n_blocks, wl.n_req
+    h = torch.zeros(N, dtype=torch.int64, device="cuda")
+    v = torch.zeros(N, dtype=torch.int64, device="cuda")
+    m = torch.zeros(R, dtype=torch.int32, device="cuda")
+    vals = torch.zeros(N, dtype=torch.int64, device="cuda")
+    storage = torch.empty(aibx.aibx_index_storage_bytes(1 << 14), dtype=torch.uint8, device="cuda")
+    ix = aibx.aibx_index_create(storage, 1 << 14)
+    pool = torch.from_numpy(np.random.default_rng(0).integers(0, 256, size=g.pool_bytes, dtype=np.uint8)).cuda()
+    desc = aibx.make_pool_desc(pool, *g.as_tuple())
+    n = 300
+    pages = torch.from_numpy(np.random.default_rng(1).permutation(g.n_pages)[:n].astype(np.int32)).cuda()
+    back = torch.from_numpy(np.random.default_rng(2).permutation(g.n_pages)[:n].astype(np.int32)).cuda()
+    staging = torch.zeros(n * g.blk_bytes, dtype=torch.uint8, device="cuda")
+
+    def sequence():
+        aibx.aibx_index_clear(ix)
+        aibx.aibx_block_hash(d_tok, d_to, d_bo, R, N, wl.block_size, 0, h)
+        aibx.aibx_index_insert(ix, h, vals, N, None)
+        aibx.aibx_index_evict(ix, evict_keys, evict_keys.numel(), ev, None)
+        aibx.aibx_prefix_match(ix, h, d_bo, R, N, v, m)
+        aibx.aibx_kv_gather(desc, pages, None, n, staging, g.blk_bytes, None)
+        aibx.aibx_kv_scatter(desc, back, None, n, staging, g.blk_bytes, None)
+
+    # Requests share prefixes, so the batch repeats keys: values are a function of the key and the
+    # evicted keys are distinct, which makes every output independent of the order of equal keys.
+    aibx.aibx_block_hash(d_tok, d_to, d_bo, R, N, wl.block_size, 0, h)
+    vals.copy_(h & 0xFFFF)
+    evict_keys = torch.unique(h)[::3].contiguous()
+    ev = torch.zeros_like(evict_keys)
+    pool0 = pool.clone()
+    sequence()
+    torch.cuda.synchronize()
+    want = [x.clone() for x in (h, v, m, ev, staging, pool)]
+    assert int((v == -1).sum()) > 0 and int((v != -1).sum()) > 0
+
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    pool.copy_(pool0)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            sequence()
+    for replay in range(3):
+        for x in (h, v, ev, staging):
+            x.zero_()                                   # eager work between the replays
+        m.fill_(-1)
+        pool.copy_(pool0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, w in zip((h, v, m, ev, staging, pool), want):
+            assert torch.equal(got, w), replay
+    aibx.aibx_index_destroy(ix)
+
+
 # ---- whole flows on the small configs ----------------------------------------------------------
 @pytest.mark.parametrize("cfg", [1, 3, 4])
 def test_flow_match_roundtrip_small(cfg):
