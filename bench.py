@@ -303,37 +303,36 @@ def survey_config(torch, aibx, cfg, layout=None):
         torch.cuda.synchronize()
         walls.append(max(e0.elapsed_time(e1), e0.elapsed_time(e2)))
     out["two_stream_gather_scatter_GBps"] = 2 * traffic / sorted(walls)[len(walls) // 2] / 1e6
-    # host tier: offload / onload of 1024 blocks through pinned host memory, 64-block chunks
+    # host tier: offload / onload of 1024 blocks straight between the pool and pinned host memory
     nh = min(1024, n)
-    chunk = 64
     h_buf = torch.empty(nh * g.blk_bytes, dtype=torch.uint8).pin_memory()
-    st2 = staging[: 2 * chunk * g.blk_bytes]
-
     h_buf.zero_()                                     # first touch of the pinned pages is not timed
 
-    def tier(fn):
+    def wall(fn):
         ts = []
         for _ in range(5):
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            fn(desc, pa, nh, st2, chunk, g.blk_bytes, h_buf, g.blk_bytes, None, s1, s2)
-            s1.synchronize()
-            s2.synchronize()
+            fn()
+            torch.cuda.synchronize()
             ts.append(time.perf_counter() - t0)
         return sorted(ts)[2]
-    t_off, t_on = tier(aibx.aibx_kv_offload), tier(aibx.aibx_kv_onload)
-    plain = []
-    for _ in range(3):
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        h_buf.copy_(staging[: h_buf.numel()], non_blocking=True)
-        torch.cuda.synchronize()
-        plain.append(time.perf_counter() - t0)
-    t_plain = sorted(plain)[1]
-    out["host_tier"] = {"blocks": nh, "chunk_blocks": chunk, "offload_GBps": nh * g.blk_bytes / t_off / 1e9,
-                        "onload_GBps": nh * g.blk_bytes / t_on / 1e9,
-                        "plain_d2h_copy_GBps": nh * g.blk_bytes / t_plain / 1e9,
-                        "offload_vs_plain_transfer": t_plain / t_off}
+    t_off = wall(lambda: aibx.aibx_kv_offload(desc, pa, nh, h_buf, g.blk_bytes))
+    t_on = wall(lambda: aibx.aibx_kv_onload(desc, pa, nh, h_buf, g.blk_bytes))
+    t_d2h = wall(lambda: h_buf.copy_(staging[: h_buf.numel()], non_blocking=True))
+    t_h2d = wall(lambda: staging[: h_buf.numel()].copy_(h_buf, non_blocking=True))
+    # a gather beside an offload: what the small grid of the host-tier kernel leaves to other streams
+    ms_alone, _ = time_calls(torch, lambda: aibx.aibx_kv_gather(desc, pb, sb, n, staging, g.blk_bytes), 5)
+    aibx.aibx_kv_offload(desc, pa, nh, h_buf, g.blk_bytes, None, s1)
+    with torch.cuda.stream(s2):
+        ms_beside, _ = time_calls(torch, lambda: aibx.aibx_kv_gather(desc, pb, sb, n, staging, g.blk_bytes, None, s2),
+                                  5, warm=0)
+    torch.cuda.synchronize()
+    hb = nh * g.blk_bytes
+    out["host_tier"] = {"blocks": nh, "offload_GBps": hb / t_off / 1e9, "onload_GBps": hb / t_on / 1e9,
+                        "plain_d2h_copy_GBps": hb / t_d2h / 1e9, "plain_h2d_copy_GBps": hb / t_h2d / 1e9,
+                        "gather_alone_GBps": traffic / ms_alone / 1e6,
+                        "gather_beside_offload_GBps": traffic / ms_beside / 1e6}
     del h_buf
     del pool, staging
     torch.cuda.empty_cache()
@@ -365,7 +364,28 @@ def survey_config(torch, aibx, cfg, layout=None):
                              flush)
     ms_f, _ = time_calls(torch, lambda: aibx.aibx_hash_match(ix, d_tok, d_to, d_bo, R, N, B, 0, None, v, m), 20)
     del flush
-    out["native"] = {"requests": R, "blocks": N, "hash_us": ms_h * 1e3, "match_us": ms_m * 1e3,
+    # hash -> insert -> match -> evict of the batch's keys: four launches, eager and as one HIP graph
+    ev_all = torch.empty(N, dtype=torch.int64, device="cuda")
+
+    def metadata_sequence():
+        aibx.aibx_block_hash(d_tok, d_to, d_bo, R, N, B, 0, h)
+        aibx.aibx_index_insert(ix, h, vals, N, c[0:3])
+        aibx.aibx_prefix_match(ix, h, d_bo, R, N, v, m)
+        aibx.aibx_index_evict(ix, h, N, ev_all, c[3:5])
+    ms_seq, _ = time_calls(torch, metadata_sequence, 20)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            metadata_sequence()
+    torch.cuda.synchronize()
+    ms_graph, _ = time_calls(torch, graph.replay, 20)
+    del graph
+    aibx.aibx_index_insert(ix, h, vals, N, c[0:3])    # the sequence ends with the batch evicted
+    out["native"] = {"metadata_sequence_4_launches_us": ms_seq * 1e3,
+                     "metadata_sequence_graph_replay_us": ms_graph * 1e3,
+                     "requests": R, "blocks": N, "hash_us": ms_h * 1e3, "match_us": ms_m * 1e3,
                      "hash_match_one_launch_us": ms_f * 1e3, "cold_cache_hash_us": cold_h * 1e3,
                      "cold_cache_match_us": cold_m * 1e3, "cold_cache_hash_match_one_launch_us": cold_f * 1e3}
     # update rates: evict then re-insert q filler keys (rounds of the 1:1:4 mix use q = 4096)
@@ -413,10 +433,12 @@ def survey_config(torch, aibx, cfg, layout=None):
     m = torch.empty(Rs, dtype=torch.int32, device="cuda")
     ms_h, _ = time_calls(torch, lambda: aibx.aibx_block_hash(d_tok, d_to, d_bo, Rs, Ns, B, 0, h), 10)
     ms_m, _ = time_calls(torch, lambda: aibx.aibx_prefix_match(ix, h, d_bo, Rs, Ns, v, m), 10)
+    ms_f, _ = time_calls(torch, lambda: aibx.aibx_hash_match(ix, d_tok, d_to, d_bo, Rs, Ns, B, 0, h, v, m), 10)
     per = 4 * B + 8 + 8 + 64 + 8
     rate = Ns / ((ms_h + ms_m) * 1e-3)
     out["scaled"] = {"requests": Rs, "blocks": Ns, "hash_ms": ms_h, "match_ms": ms_m, "blocks_per_s": rate,
                      "roofline_frac": rate * per / 1e9 / HBM_PEAK_GBPS, "bytes_per_block": per,
+                     "one_launch_ms": ms_f, "one_launch_roofline_frac": Ns / (ms_f * 1e-3) * per / 1e9 / HBM_PEAK_GBPS,
                      "index_slots": wl.n_slots, "load_factor": wl.load_factor}
     # routing decision on the scaled batch: values read as pod sets (low 8 bits), 8 pods
     pod_sets = torch.where(v == -1, v, v & 0xFF)

@@ -15,7 +15,7 @@
  *   aibx_index_touch / _age / _select_victims   scan-resistant victim selection (Section 3.2.5)
  *   aibx_kv_gather     paged KV pool -> contiguous staging (offload)     (Section 3.2.5)
  *   aibx_kv_scatter    contiguous staging -> paged KV pool (onload)      (Section 3.2.5)
- *   aibx_kv_offload / aibx_kv_onload   the same through to pinned host memory, pipelined
+ *   aibx_kv_offload / aibx_kv_onload   paged KV pool <-> pinned host memory, one kernel each way
  *
  * The paper prints no hash function, index layout or copy layout; the rules stated below are
  * this library's own and are what its results are checked against.
@@ -257,31 +257,28 @@ int aibx_kv_scatter(const aibx_pool_desc* pool, const int32_t* d_page_ids,
                     uint64_t staging_block_stride, uint64_t* d_bad_page_counter, void* stream);
 
 /* ------------------------------------------------------------------------------------------
- * Host-tier leg: paged pool <-> pinned host memory through a two-part staging buffer in HBM.
- * (Section 3.2.5: the cache pool is DRAM-based and exchanges KV with the colocated engine through
- * host memory.) Offload: chunks of `chunk_blocks` pages are gathered into the two halves of
- * d_staging in turn on stream_copy, and each gathered chunk is sent to host memory on stream_xfer
- * while the next one is gathered. Onload is the mirror image: chunk k travels host -> staging on
- * stream_xfer while chunk k-1 is scattered on stream_copy.
- *   Entry i moves page d_page_ids[i] <-> host block i at h_buf + i*host_block_stride (the n_seg
- *   segments back to back, as in a staging block). Holes and out-of-range pages are skipped as in
- *   aibx_kv_gather/_scatter; on offload the host block of a skipped entry receives unspecified bytes.
- *   d_staging: 2*chunk_blocks*staging_block_stride bytes of device memory, 16-byte aligned.
- *   h_dst / h_src: HOST memory, pinned (page-locked) for the transfer to be asynchronous, 16-byte
- *   aligned; host_block_stride multiple of 16, >= n_seg*seg_bytes. stream_copy != stream_xfer.
- * The calls only enqueue. When aibx_kv_offload returns, everything is ordered before later work on
- * stream_copy (it waits for the transfers); when aibx_kv_onload returns, the last scatter is on
- * stream_copy and stream_xfer has been made to start after the work already queued on stream_copy.
- * The staging buffer and the host buffer must stay untouched until stream_copy has drained.
- * Errors: INVALID_ARG, ALIGN, HIP. */
-int aibx_kv_offload(const aibx_pool_desc* pool, const int32_t* d_page_ids, int64_t n, void* d_staging,
-                    int64_t chunk_blocks, uint64_t staging_block_stride, void* h_dst,
-                    uint64_t host_block_stride, uint64_t* d_bad_page_counter, void* stream_copy,
-                    void* stream_xfer);
-int aibx_kv_onload(const aibx_pool_desc* pool, const int32_t* d_page_ids, int64_t n, void* d_staging,
-                   int64_t chunk_blocks, uint64_t staging_block_stride, const void* h_src,
-                   uint64_t host_block_stride, uint64_t* d_bad_page_counter, void* stream_copy,
-                   void* stream_xfer);
+ * Host-tier leg: paged pool <-> pinned host memory, moved by one kernel that addresses the host
+ * buffer directly. (Section 3.2.5: the cache pool is DRAM-based and exchanges KV with the
+ * colocated engine through host memory.)
+ *   Entry i < n moves page p = d_page_ids[i] <-> host block i at h_buf + i*host_block_stride (the
+ *   n_seg segments back to back, as in a staging block). aibx_kv_offload: host block i <- page p;
+ *   aibx_kv_onload: page p <- host block i. p < 0 marks a hole and p >= n_pages is counted in
+ *   *d_bad_page_counter (device uint64, nullable), as in aibx_kv_gather/_scatter; either way the
+ *   entry is skipped and neither its host block nor any page is touched. Entries of one onload
+ *   call must not share a page. Bytes between host blocks (stride > block) are never written.
+ *   h_dst / h_src: HOST memory that is pinned and mapped for the GPU (hipHostMalloc, or what a
+ *   framework allocates through it), 16-byte aligned, at least (n-1)*host_block_stride +
+ *   n_seg*seg_bytes bytes inside one allocation; host_block_stride multiple of 16, >=
+ *   n_seg*seg_bytes. Pageable memory, device memory and buffers that are too short are refused
+ *   with INVALID_ARG before anything is launched.
+ * The call only enqueues one launch on `stream`, with a small fixed grid sized for the host link,
+ * so kernels on other streams keep running beside it. The host buffer holds the data (offload) or
+ * may be reused (onload) once `stream` has drained past the call.
+ * Errors: INVALID_ARG, ALIGN, UNSUPPORTED (a block of 2^31 or more 4 KiB pieces), HIP. */
+int aibx_kv_offload(const aibx_pool_desc* pool, const int32_t* d_page_ids, int64_t n, void* h_dst,
+                    uint64_t host_block_stride, uint64_t* d_bad_page_counter, void* stream);
+int aibx_kv_onload(const aibx_pool_desc* pool, const int32_t* d_page_ids, int64_t n, const void* h_src,
+                   uint64_t host_block_stride, uint64_t* d_bad_page_counter, void* stream);
 
 #ifdef __cplusplus
 }

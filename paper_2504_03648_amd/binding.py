@@ -74,7 +74,7 @@ def load(build_if_missing: bool = True):
     for f in (lib.aibx_kv_gather, lib.aibx_kv_scatter):
         f.argtypes = [C.POINTER(PoolDesc), vp, vp, i64, vp, u64, vp, vp]
     for f in (lib.aibx_kv_offload, lib.aibx_kv_onload):
-        f.argtypes = [C.POINTER(PoolDesc), vp, i64, vp, i64, u64, vp, u64, vp, vp, vp]
+        f.argtypes = [C.POINTER(PoolDesc), vp, i64, vp, u64, vp, vp]
     for name in EXPORTS[4:]:
         getattr(lib, name).restype = C.c_int
     _lib = lib
@@ -225,24 +225,19 @@ def aibx_kv_scatter(pool: PoolDesc, d_page_ids, d_slot_ids, n, d_staging, stagin
 
 
 def _host_ptr(t):
+    """Address of a host tensor; the library itself refuses memory that is not pinned."""
     if not isinstance(t, torch.Tensor) or t.is_cuda or not t.is_contiguous():
         raise ValueError("expected a contiguous host tensor")
-    if not t.is_pinned():
-        raise ValueError("the host buffer must be pinned memory (torch.empty(..., pin_memory=True))")
     return C.c_void_p(t.data_ptr())
 
 
-def aibx_kv_offload(pool: PoolDesc, d_page_ids, n, d_staging, chunk_blocks, staging_block_stride, h_dst,
-                    host_block_stride, d_bad_page_counter, stream_copy, stream_xfer):
+def aibx_kv_offload(pool: PoolDesc, d_page_ids, n, h_dst, host_block_stride, d_bad_page_counter=None, stream=None):
     _check("aibx_kv_offload", load().aibx_kv_offload(
-        C.byref(pool), _p(d_page_ids, torch.int32), int(n), _p(d_staging), int(chunk_blocks),
-        int(staging_block_stride), _host_ptr(h_dst), int(host_block_stride), _p(d_bad_page_counter, U64),
-        _s(stream_copy), _s(stream_xfer)))
+        C.byref(pool), _p(d_page_ids, torch.int32), int(n), _host_ptr(h_dst), int(host_block_stride),
+        _p(d_bad_page_counter, U64), _s(stream)))
 
 
-def aibx_kv_onload(pool: PoolDesc, d_page_ids, n, d_staging, chunk_blocks, staging_block_stride, h_src,
-                   host_block_stride, d_bad_page_counter, stream_copy, stream_xfer):
+def aibx_kv_onload(pool: PoolDesc, d_page_ids, n, h_src, host_block_stride, d_bad_page_counter=None, stream=None):
     _check("aibx_kv_onload", load().aibx_kv_onload(
-        C.byref(pool), _p(d_page_ids, torch.int32), int(n), _p(d_staging), int(chunk_blocks),
-        int(staging_block_stride), _host_ptr(h_src), int(host_block_stride), _p(d_bad_page_counter, U64),
-        _s(stream_copy), _s(stream_xfer)))
+        C.byref(pool), _p(d_page_ids, torch.int32), int(n), _host_ptr(h_src), int(host_block_stride),
+        _p(d_bad_page_counter, U64), _s(stream)))

@@ -1,138 +1,133 @@
 // Host-tier leg of offload / onload (Section 3.2.5 of the paper: the cache pool lives in DRAM and
-// exchanges KV with the colocated engine through host memory). The paged pool is gathered into a
-// two-part staging buffer in HBM chunk by chunk, and each chunk travels to pinned host memory on a
-// second stream while the next chunk is being gathered (and the reverse for onload), so the PCIe
-// transfer - the slow leg by two orders of magnitude - never waits for the copy kernels.
-// Host code only: the device work is aibx_kv_gather / aibx_kv_scatter and the runtime's copies.
-#include <vector>
-
+// exchanges KV with the colocated engine through host memory).
+//
+// One kernel moves pages straight between the paged pool in HBM and pinned host memory, which the
+// GPU addresses directly: no staging buffer, no second stream, no events. The link to the host is
+// slower than HBM by two orders of magnitude, so the kernel is sized for the link, not for the
+// chip: a fixed, small grid whose workgroups walk the tiles in order. Measured on MI355X, 64
+// workgroups already reach what the link gives (55.7 GB/s towards the host, 57.6 GB/s from it - the
+// rate of one large library copy of pinned memory), more than 256 gain nothing, and 128 workgroups
+// of 4 waves hold about 6 % of the chip's wave slots, so kernels on other streams keep running
+// beside a transfer. A pipeline of gather launches and chunked library copies on two streams
+// reached the same rate at best, and half of it in runs where the runtime's chunk copies slowed
+// down; the direct kernel did not show that second mode.
 #include "common.h"
 
 namespace aibx {
 namespace {
 
-struct Events {
-  std::vector<hipEvent_t> ev;
-  ~Events() {
-    for (hipEvent_t e : ev) (void)hipEventDestroy(e);  // pending work keeps its own reference
-  }
-  int make(hipEvent_t* out) {
-    hipError_t e = hipEventCreateWithFlags(out, hipEventDisableTiming);
-    if (e != hipSuccess) return hip_failed(e);
-    ev.push_back(*out);
-    return AIBX_OK;
-  }
+struct HostCopyArgs {
+  unsigned char* pool;
+  unsigned char* host;  // the GPU's view of the pinned host buffer
+  u64* bad_page;        // nullable
+  u64 seg_stride, page_stride, seg_bytes, host_stride;
+  int64_t n_pages;
+  u64 total_tiles;      // n * tiles_per_block
+  u32 chunks_per_seg;
+  u32 tiles_per_block;  // chunks_per_seg * n_seg
 };
 
-#define AIBX_HIP(call)                            \
-  do {                                            \
-    hipError_t e_ = (call);                       \
-    if (e_ != hipSuccess) return hip_failed(e_);  \
-  } while (0)
+constexpr int kHostThreads = 256;          // one 16-byte vector per lane: 4 KiB tiles
+constexpr unsigned kHostWorkgroups = 128;  // enough to keep the link busy, see above
 
-// One chunk between staging and host: a linear copy when both sides are densely packed, a pitched
-// copy otherwise.
-hipError_t copy_chunk(void* dst, u64 dst_stride, const void* src, u64 src_stride, u64 blk_bytes, int64_t m,
-                      hipMemcpyKind kind, hipStream_t st) {
-  if (dst_stride == blk_bytes && src_stride == blk_bytes) return hipMemcpyAsync(dst, src, blk_bytes * (u64)m, kind, st);
-  return hipMemcpy2DAsync(dst, dst_stride, src, src_stride, blk_bytes, (size_t)m, kind, st);
+typedef __attribute__((ext_vector_type(4))) u32 vec16;
+
+// Tile t = (entry i, segment s, chunk c) in that order, so neighbouring workgroups write
+// neighbouring 4 KiB pieces of a host block. kToHost: pool -> host (offload), else host -> pool.
+template <bool kToHost>
+__global__ __launch_bounds__(kHostThreads) void kv_host_copy_kernel(HostCopyArgs a,
+                                                                     const int32_t* __restrict__ page_ids) {
+  for (u64 t = blockIdx.x; t < a.total_tiles; t += gridDim.x) {
+    const u64 i = t / a.tiles_per_block;
+    const u32 tile_in_block = (u32)(t - i * a.tiles_per_block);
+    const int64_t p = page_ids[i];
+    if (p < 0) continue;  // hole
+    if (p >= a.n_pages) {
+      if (tile_in_block == 0 && threadIdx.x == 0 && a.bad_page) atomicAdd((unsigned long long*)a.bad_page, 1ull);
+      continue;
+    }
+    const u32 s = tile_in_block / a.chunks_per_seg;
+    const u32 c = tile_in_block - s * a.chunks_per_seg;
+    const u64 off = ((u64)c * kHostThreads + threadIdx.x) * 16;
+    if (off >= a.seg_bytes) continue;  // ragged last chunk of a segment
+    vec16* in_pool = reinterpret_cast<vec16*>(a.pool + (u64)s * a.seg_stride + (u64)p * a.page_stride + off);
+    vec16* in_host = reinterpret_cast<vec16*>(a.host + i * a.host_stride + (u64)s * a.seg_bytes + off);
+    if (kToHost)
+      *in_host = *in_pool;
+    else
+      *in_pool = *in_host;
+  }
 }
 
-int check_tier_args(const aibx_pool_desc* pool, const int32_t* d_page_ids, int64_t n, void* d_staging,
-                    int64_t chunk_blocks, u64 staging_stride, void* h_buf, u64 host_stride, void* s_copy,
-                    void* s_xfer) {
-  if (n < 0 || chunk_blocks < 1) return AIBX_ERR_INVALID_ARG;
+template <bool kToHost>
+int launch_host_copy(const aibx_pool_desc* pool, const int32_t* d_page_ids, int64_t n, void* h_buf, u64 host_stride,
+                     u64* d_bad, void* stream) {
+  if (n < 0) return AIBX_ERR_INVALID_ARG;
   if (n == 0) return AIBX_OK;
-  if (!pool || !d_page_ids || !d_staging || !h_buf) return AIBX_ERR_INVALID_ARG;
-  if (pool->n_seg < 1 || pool->seg_bytes == 0) return AIBX_ERR_INVALID_ARG;
+  if (!pool || !pool->base || !d_page_ids || !h_buf) return AIBX_ERR_INVALID_ARG;
+  if (pool->n_seg < 1 || pool->seg_bytes == 0 || pool->n_pages < 0) return AIBX_ERR_INVALID_ARG;
+  if (pool->page_stride < pool->seg_bytes) return AIBX_ERR_INVALID_ARG;
   const u64 blk_bytes = (u64)pool->n_seg * pool->seg_bytes;
-  if (staging_stride < blk_bytes || host_stride < blk_bytes) return AIBX_ERR_INVALID_ARG;
-  if (s_copy == s_xfer) return AIBX_ERR_INVALID_ARG;  // the overlap needs two streams
-  if (!aligned(h_buf, 16) || host_stride % 16) return AIBX_ERR_ALIGN;
-  return 1;  // proceed
+  if (blk_bytes / pool->seg_bytes != (u64)pool->n_seg || host_stride < blk_bytes) return AIBX_ERR_INVALID_ARG;
+  if (!aligned(pool->base, 16) || !aligned(h_buf, 16) || pool->seg_bytes % 16 || pool->seg_stride % 16 ||
+      pool->page_stride % 16 || host_stride % 16)
+    return AIBX_ERR_ALIGN;
+  if (!aligned(d_page_ids, 4) || !aligned(d_bad, 8)) return AIBX_ERR_ALIGN;
+  if ((u64)(n - 1) > (~0ull - blk_bytes) / host_stride) return AIBX_ERR_INVALID_ARG;
+  const u64 extent = (u64)(n - 1) * host_stride + blk_bytes;  // bytes of the host buffer the call may touch
+
+  // The kernel dereferences the host buffer, so it has to be pinned memory the GPU can address,
+  // and long enough: anything else is refused here rather than left to fault on the GPU.
+  void* dev_view = nullptr;
+  if (hipHostGetDevicePointer(&dev_view, h_buf, 0) != hipSuccess || !dev_view) {
+    (void)hipGetLastError();
+    return AIBX_ERR_INVALID_ARG;  // not pinned host memory
+  }
+  hipDeviceptr_t range_base = nullptr;
+  size_t range_bytes = 0;
+  if (hipMemGetAddressRange(&range_base, &range_bytes, dev_view) != hipSuccess) {
+    (void)hipGetLastError();
+    return AIBX_ERR_INVALID_ARG;
+  }
+  const u64 lead = (u64)(static_cast<unsigned char*>(dev_view) - static_cast<unsigned char*>(range_base));
+  if (lead > range_bytes || extent > range_bytes - lead) return AIBX_ERR_INVALID_ARG;  // buffer too short
+
+  const u64 tile_bytes = (u64)kHostThreads * 16;
+  const u64 cps = (pool->seg_bytes + tile_bytes - 1) / tile_bytes;
+  const u64 tpb = cps * (u64)pool->n_seg;
+  if (tpb > 0x7FFFFFF0ull) return AIBX_ERR_UNSUPPORTED;
+
+  HostCopyArgs a;
+  a.pool = static_cast<unsigned char*>(pool->base);
+  a.host = static_cast<unsigned char*>(dev_view);
+  a.bad_page = d_bad;
+  a.seg_stride = pool->seg_stride;
+  a.page_stride = pool->page_stride;
+  a.seg_bytes = pool->seg_bytes;
+  a.host_stride = host_stride;
+  a.n_pages = pool->n_pages;
+  a.total_tiles = (u64)n * tpb;
+  a.chunks_per_seg = (u32)cps;
+  a.tiles_per_block = (u32)tpb;
+  const unsigned grid = a.total_tiles < kHostWorkgroups ? (unsigned)a.total_tiles : kHostWorkgroups;
+  kv_host_copy_kernel<kToHost><<<dim3(grid), kHostThreads, 0, as_stream(stream)>>>(a, d_page_ids);
+  return launch_status();
 }
 
 }  // namespace
 }  // namespace aibx
 
-using namespace aibx;
-
 extern "C" {
 
-int aibx_kv_offload(const aibx_pool_desc* pool, const int32_t* d_page_ids, int64_t n, void* d_staging,
-                    int64_t chunk_blocks, uint64_t staging_block_stride, void* h_dst,
-                    uint64_t host_block_stride, uint64_t* d_bad_page_counter, void* stream_copy,
-                    void* stream_xfer) {
-  const int pre = check_tier_args(pool, d_page_ids, n, d_staging, chunk_blocks, staging_block_stride, h_dst,
-                                  host_block_stride, stream_copy, stream_xfer);
-  if (pre != 1) return pre;
-  const u64 blk_bytes = (u64)pool->n_seg * pool->seg_bytes;
-  hipStream_t sc = as_stream(stream_copy), sx = as_stream(stream_xfer);
-  Events events;
-  hipEvent_t sent[2] = {nullptr, nullptr};  // transfer that last read staging half 0 / 1
-  int64_t k = 0;
-  for (int64_t first = 0; first < n; first += chunk_blocks, ++k) {
-    const int64_t m = (n - first) < chunk_blocks ? (n - first) : chunk_blocks;
-    const int half = (int)(k & 1);
-    unsigned char* stage = static_cast<unsigned char*>(d_staging) + (u64)half * (u64)chunk_blocks * staging_block_stride;
-    if (sent[half]) AIBX_HIP(hipStreamWaitEvent(sc, sent[half], 0));  // the half is free again
-    const int rc = aibx_kv_gather(pool, d_page_ids + first, nullptr, m, stage, staging_block_stride,
-                                  d_bad_page_counter, sc);
-    if (rc != AIBX_OK) return rc;
-    hipEvent_t gathered;
-    int erc = events.make(&gathered);
-    if (erc != AIBX_OK) return erc;
-    AIBX_HIP(hipEventRecord(gathered, sc));
-    AIBX_HIP(hipStreamWaitEvent(sx, gathered, 0));
-    AIBX_HIP(copy_chunk(static_cast<unsigned char*>(h_dst) + (u64)first * host_block_stride, host_block_stride,
-                        stage, staging_block_stride, blk_bytes, m, hipMemcpyDeviceToHost, sx));
-    erc = events.make(&sent[half]);
-    if (erc != AIBX_OK) return erc;
-    AIBX_HIP(hipEventRecord(sent[half], sx));
-  }
-  for (int h = 0; h < 2; ++h)  // waiting on the copy stream now covers the transfers too
-    if (sent[h]) AIBX_HIP(hipStreamWaitEvent(sc, sent[h], 0));
-  return AIBX_OK;
+int aibx_kv_offload(const aibx_pool_desc* pool, const int32_t* d_page_ids, int64_t n, void* h_dst,
+                    uint64_t host_block_stride, uint64_t* d_bad_page_counter, void* stream) {
+  return aibx::launch_host_copy<true>(pool, d_page_ids, n, h_dst, host_block_stride, d_bad_page_counter, stream);
 }
 
-int aibx_kv_onload(const aibx_pool_desc* pool, const int32_t* d_page_ids, int64_t n, void* d_staging,
-                   int64_t chunk_blocks, uint64_t staging_block_stride, const void* h_src,
-                   uint64_t host_block_stride, uint64_t* d_bad_page_counter, void* stream_copy,
-                   void* stream_xfer) {
-  const int pre = check_tier_args(pool, d_page_ids, n, d_staging, chunk_blocks, staging_block_stride,
-                                  const_cast<void*>(h_src), host_block_stride, stream_copy, stream_xfer);
-  if (pre != 1) return pre;
-  const u64 blk_bytes = (u64)pool->n_seg * pool->seg_bytes;
-  hipStream_t sc = as_stream(stream_copy), sx = as_stream(stream_xfer);
-  Events events;
-  hipEvent_t scattered[2] = {nullptr, nullptr};  // scatter that last read staging half 0 / 1
-  hipEvent_t start;
-  int erc = events.make(&start);
-  if (erc != AIBX_OK) return erc;
-  AIBX_HIP(hipEventRecord(start, sc));  // the transfers start after what is already queued on the copy stream
-  AIBX_HIP(hipStreamWaitEvent(sx, start, 0));
-  int64_t k = 0;
-  for (int64_t first = 0; first < n; first += chunk_blocks, ++k) {
-    const int64_t m = (n - first) < chunk_blocks ? (n - first) : chunk_blocks;
-    const int half = (int)(k & 1);
-    unsigned char* stage = static_cast<unsigned char*>(d_staging) + (u64)half * (u64)chunk_blocks * staging_block_stride;
-    if (scattered[half]) AIBX_HIP(hipStreamWaitEvent(sx, scattered[half], 0));
-    AIBX_HIP(copy_chunk(stage, staging_block_stride,
-                        static_cast<const unsigned char*>(h_src) + (u64)first * host_block_stride, host_block_stride,
-                        blk_bytes, m, hipMemcpyHostToDevice, sx));
-    hipEvent_t loaded;
-    erc = events.make(&loaded);
-    if (erc != AIBX_OK) return erc;
-    AIBX_HIP(hipEventRecord(loaded, sx));
-    AIBX_HIP(hipStreamWaitEvent(sc, loaded, 0));
-    const int rc = aibx_kv_scatter(pool, d_page_ids + first, nullptr, m, stage, staging_block_stride,
-                                   d_bad_page_counter, sc);
-    if (rc != AIBX_OK) return rc;
-    erc = events.make(&scattered[half]);
-    if (erc != AIBX_OK) return erc;
-    AIBX_HIP(hipEventRecord(scattered[half], sc));
-  }
-  return AIBX_OK;
+int aibx_kv_onload(const aibx_pool_desc* pool, const int32_t* d_page_ids, int64_t n, const void* h_src,
+                   uint64_t host_block_stride, uint64_t* d_bad_page_counter, void* stream) {
+  return aibx::launch_host_copy<false>(pool, d_page_ids, n, const_cast<void*>(h_src), host_block_stride,
+                                       d_bad_page_counter, stream);
 }
 
 }  // extern "C"

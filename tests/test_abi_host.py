@@ -86,11 +86,15 @@ def test_argument_errors_are_raised_before_any_launch(lib):
     assert lib.aibx_kv_gather(C.byref(d), fake, None, 1, fake, 8200, None, None) == -2
     assert lib.aibx_kv_scatter(C.byref(d), fake, None, 1, odd, 8192, None, None) == -2
     for f in (lib.aibx_kv_offload, lib.aibx_kv_onload):
-        assert f(C.byref(d), fake, 1, fake, 0, 8192, fake, 8192, None, fake, odd) == -1      # chunk_blocks < 1
-        assert f(C.byref(d), fake, 1, fake, 4, 8192, fake, 8192, None, fake, fake) == -1     # one stream only
-        assert f(C.byref(d), fake, 1, fake, 4, 8192, fake, 4096, None, fake, odd) == -1      # host stride < block
-        assert f(C.byref(d), fake, 1, fake, 4, 8192, odd, 8192, None, fake, odd) == -2
-        assert f(C.byref(d), fake, 0, fake, 4, 8192, fake, 8192, None, fake, odd) == 0
+        assert f(C.byref(d), fake, -1, fake, 8192, None, None) == -1
+        assert f(C.byref(d), fake, 0, fake, 8192, None, None) == 0
+        assert f(None, fake, 1, fake, 8192, None, None) == -1
+        assert f(C.byref(d), fake, 1, None, 8192, None, None) == -1
+        assert f(C.byref(d), fake, 1, fake, 4096, None, None) == -1      # host stride < block
+        assert f(C.byref(d), fake, 1, odd, 8192, None, None) == -2
+        assert f(C.byref(d), fake, 1, fake, 8200, None, None) == -2
+        # an address that is not pinned host memory is refused before any launch
+        assert f(C.byref(d), fake, 1, fake, 8192, None, None) == -1
     bad = PoolDesc(0x1000, 2, 1 << 20, 4096, 4100, 16)
     assert lib.aibx_kv_gather(C.byref(bad), fake, None, 1, fake, 8208, None, None) == -1  # page_stride < seg
     bad = PoolDesc(0x1000, 2, 1 << 20, 4112, 4104, 16)

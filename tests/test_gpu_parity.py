@@ -438,42 +438,71 @@ def test_gather_then_scatter_is_identity_on_the_pool():
 
 
 # ---- host tier ----------------------------------------------------------------------------------
-@pytest.mark.parametrize("n_seg,seg_bytes,n,chunk,pad", [(6, 4096, 77, 16, 0), (1, 65536, 40, 64, 0),
-                                                         (64, 32768, 50, 7, 0), (3, 48, 33, 4, 32)])
-def test_offload_to_host_and_onload_back(n_seg, seg_bytes, n, chunk, pad):
+@pytest.mark.parametrize("n_seg,seg_bytes,n,pad", [(6, 4096, 77, 0), (1, 65536, 40, 0), (64, 32768, 50, 0),
+                                                   (3, 48, 33, 32), (2, 4096 + 16, 600, 16)])
+def test_offload_to_host_and_onload_back(n_seg, seg_bytes, n, pad):
     import torch
     import paper_2504_03648_amd as aibx
-    g = Geometry(n_seg, seg_bytes, 200)
+    n_pages = max(200, n + 50)
+    g = Geometry(n_seg, seg_bytes, n_pages)
     rng = np.random.default_rng(n_seg + n)
     host_pool = rng.integers(0, 256, size=g.pool_bytes, dtype=np.uint8)
     hb = HipBackend()
     hb.pool_create(g, None, None, host_bytes=host_pool.copy())
-    ids = rng.permutation(200)[:n].astype(np.int32)
-    ids[3], ids[5] = -1, 200                               # a hole and a bad page
+    ids = rng.permutation(n_pages)[:n].astype(np.int32)
+    ids[3], ids[5] = -1, n_pages                           # a hole and a bad page
     d_ids = torch.from_numpy(ids).cuda()
-    st_stride, h_stride = g.blk_bytes + pad, g.blk_bytes + 2 * pad
-    staging = torch.zeros(2 * chunk * st_stride, dtype=torch.uint8, device="cuda")
+    h_stride = g.blk_bytes + pad
     h_buf = torch.full((n * h_stride,), 0x3C, dtype=torch.uint8).pin_memory()
     bad = torch.zeros(1, dtype=torch.int64, device="cuda")
-    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    aibx.aibx_kv_offload(hb.desc, d_ids, n, h_buf, h_stride, bad)
     torch.cuda.synchronize()
-    aibx.aibx_kv_offload(hb.desc, d_ids, n, staging, chunk, st_stride, h_buf, h_stride, bad, s1, s2)
-    s1.synchronize()
+    # the oracle's gather with slot i = entry i: skipped entries and the padding keep their bytes
     want = np.full(n * h_stride, 0x3C, dtype=np.uint8)
     assert oracle.kv_gather(host_pool, g.as_tuple(), ids, None, want, h_stride) == 1
-    got = h_buf.numpy().reshape(n, h_stride)
+    assert np.array_equal(h_buf.numpy(), want)
+    assert int(bad.item()) == 1
+    # wipe the moved pages, put other bytes where the skipped entries' host blocks are, onload
     moved = np.ones(n, dtype=bool)
     moved[[3, 5]] = False
-    assert np.array_equal(got[moved][:, : g.blk_bytes], want.reshape(n, h_stride)[moved][:, : g.blk_bytes])
-    assert np.all(got[:, g.blk_bytes:] == 0x3C)            # padding between host blocks untouched
-    assert int(bad.item()) == 1
-    # wipe the moved pages, bring them back from the host copy
     hb.fill_pages(ids[moved], 0xA5)
-    aibx.aibx_kv_onload(hb.desc, d_ids, n, staging, chunk, st_stride, h_buf, h_stride, bad, s1, s2)
-    s1.synchronize()
-    s2.synchronize()
+    aibx.aibx_kv_onload(hb.desc, d_ids, n, h_buf, h_stride, bad)
+    torch.cuda.synchronize()
     assert np.array_equal(hb.pool.cpu().numpy(), host_pool)
     assert int(bad.item()) == 2
+    # onload of other bytes against the oracle's scatter
+    fresh = rng.integers(0, 256, size=n * h_stride, dtype=np.uint8)
+    h_buf.copy_(torch.from_numpy(fresh))
+    aibx.aibx_kv_onload(hb.desc, d_ids, n, h_buf, h_stride, None)
+    torch.cuda.synchronize()
+    assert oracle.kv_scatter(host_pool, g.as_tuple(), ids, None, fresh, h_stride) == 1
+    assert np.array_equal(hb.pool.cpu().numpy(), host_pool)
+
+
+def test_host_tier_refuses_memory_the_gpu_cannot_address():
+    import torch
+    import paper_2504_03648_amd as aibx
+    g = Geometry(4, 4096, 64)
+    hb = HipBackend()
+    hb.pool_create(g, "bf16", 1)
+    ids = torch.arange(8, dtype=torch.int32, device="cuda")
+    pageable = torch.zeros(8 * g.blk_bytes, dtype=torch.uint8)
+    pinned = torch.zeros(8 * g.blk_bytes, dtype=torch.uint8).pin_memory()
+    keep = hb.pool.clone()
+    for fn in (aibx.aibx_kv_offload, aibx.aibx_kv_onload):
+        with pytest.raises(aibx.AibxError) as e:
+            fn(hb.desc, ids, 8, pageable, g.blk_bytes)
+        assert e.value.status == -1
+        with pytest.raises(aibx.AibxError) as e:          # 1 GiB of host blocks claimed, 128 KiB allocated
+            fn(hb.desc, ids, 8, pinned, 1 << 27)
+        assert e.value.status == -1
+    torch.cuda.synchronize()
+    assert torch.equal(hb.pool, keep) and int(pinned.sum()) == 0
+    aibx.aibx_kv_offload(hb.desc, ids, 8, pinned, g.blk_bytes)       # the library still works afterwards
+    torch.cuda.synchronize()
+    want = np.zeros(8 * g.blk_bytes, dtype=np.uint8)
+    oracle.kv_gather(hb.pool.cpu().numpy(), g.as_tuple(), ids.cpu().numpy(), None, want, g.blk_bytes)
+    assert np.array_equal(pinned.numpy(), want)
 
 
 # ---- HIP graph capture ----------------------------------------------------------------------------
