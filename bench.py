@@ -321,18 +321,36 @@ def survey_config(torch, aibx, cfg, layout=None):
     t_on = wall(lambda: aibx.aibx_kv_onload(desc, pa, nh, h_buf, g.blk_bytes))
     t_d2h = wall(lambda: h_buf.copy_(staging[: h_buf.numel()], non_blocking=True))
     t_h2d = wall(lambda: staging[: h_buf.numel()].copy_(h_buf, non_blocking=True))
-    # a gather beside an offload: what the small grid of the host-tier kernel leaves to other streams
+    # gathers on a second stream while an offload / onload runs: the rate they keep, and the transfer's
+    def beside(fn):
+        k = max(2, min(64, int(1.2 * (nh * g.blk_bytes / 55e9) / (ms_alone * 1e-3))))
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(k)]
+        t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0.record(s1)
+        fn(desc, pa, nh, h_buf, g.blk_bytes, None, s1)
+        t1.record(s1)
+        for a, b in evs:
+            a.record(s2)
+            aibx.aibx_kv_gather(desc, pb, sb, n, staging, g.blk_bytes, None, s2)
+            b.record(s2)
+        torch.cuda.synchronize()
+        span, used, rates = t0.elapsed_time(t1), 0.0, []
+        for a, b in evs:
+            used += a.elapsed_time(b)
+            if used <= span:
+                rates.append(traffic / a.elapsed_time(b) / 1e6)
+        rates.sort()
+        return {"transfer_GBps": nh * g.blk_bytes / span / 1e6, "gathers_inside": len(rates),
+                "gather_median_GBps": rates[len(rates) // 2] if rates else None,
+                "gather_min_GBps": rates[0] if rates else None}
     ms_alone, _ = time_calls(torch, lambda: aibx.aibx_kv_gather(desc, pb, sb, n, staging, g.blk_bytes), 5)
-    aibx.aibx_kv_offload(desc, pa, nh, h_buf, g.blk_bytes, None, s1)
-    with torch.cuda.stream(s2):
-        ms_beside, _ = time_calls(torch, lambda: aibx.aibx_kv_gather(desc, pb, sb, n, staging, g.blk_bytes, None, s2),
-                                  5, warm=0)
-    torch.cuda.synchronize()
+    b_off, b_on = beside(aibx.aibx_kv_offload), beside(aibx.aibx_kv_onload)
     hb = nh * g.blk_bytes
     out["host_tier"] = {"blocks": nh, "offload_GBps": hb / t_off / 1e9, "onload_GBps": hb / t_on / 1e9,
                         "plain_d2h_copy_GBps": hb / t_d2h / 1e9, "plain_h2d_copy_GBps": hb / t_h2d / 1e9,
                         "gather_alone_GBps": traffic / ms_alone / 1e6,
-                        "gather_beside_offload_GBps": traffic / ms_beside / 1e6}
+                        "beside_offload": b_off, "beside_onload": b_on}
     del h_buf
     del pool, staging
     torch.cuda.empty_cache()

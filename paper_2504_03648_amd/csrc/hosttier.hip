@@ -4,13 +4,18 @@
 // One kernel moves pages straight between the paged pool in HBM and pinned host memory, which the
 // GPU addresses directly: no staging buffer, no second stream, no events. The link to the host is
 // slower than HBM by two orders of magnitude, so the kernel is sized for the link, not for the
-// chip: a fixed, small grid whose workgroups walk the tiles in order. Measured on MI355X, 64
-// workgroups already reach what the link gives (55.7 GB/s towards the host, 57.6 GB/s from it - the
-// rate of one large library copy of pinned memory), more than 256 gain nothing, and 128 workgroups
-// of 4 waves hold about 6 % of the chip's wave slots, so kernels on other streams keep running
-// beside a transfer. A pipeline of gather launches and chunked library copies on two streams
-// reached the same rate at best, and half of it in runs where the runtime's chunk copies slowed
-// down; the direct kernel did not show that second mode.
+// chip: a fixed, small grid whose workgroups walk the tiles in order. Two things decide how it
+// behaves beside other kernels, both measured on MI355X with an HBM-bound copy running on a
+// second stream (6.5 TB/s alone):
+//  - Stores to host memory are written through at system scope. Plain (or non-temporal) stores
+//    reach the same link rate, but the copy on the other stream then stalls for milliseconds at a
+//    time (single launches at 0.2-1.3 TB/s); with system-scope stores it never dropped below 6.1.
+//  - 32 workgroups. The link is full from about 24-32 workgroups on (55.8 GB/s towards the host,
+//    54.6-57.2 GB/s from it; one large library copy of pinned memory: 57.1 / 57.6), and every
+//    further workgroup only adds requests that wait for the link inside the memory system: at 32
+//    the copy beside it keeps 96 % of its rate, at 48 it loses 7-28 %, at 128 most of it.
+// A pipeline of gather launches and chunked library copies on two streams reached the same rate at
+// best, and half of it in runs where the runtime's chunk copies slowed down.
 #include "common.h"
 
 namespace aibx {
@@ -28,7 +33,7 @@ struct HostCopyArgs {
 };
 
 constexpr int kHostThreads = 256;          // one 16-byte vector per lane: 4 KiB tiles
-constexpr unsigned kHostWorkgroups = 128;  // enough to keep the link busy, see above
+constexpr unsigned kHostWorkgroups = 32;   // fills the link and leaves the memory system to others, see above
 
 typedef __attribute__((ext_vector_type(4))) u32 vec16;
 
@@ -52,10 +57,12 @@ __global__ __launch_bounds__(kHostThreads) void kv_host_copy_kernel(HostCopyArgs
     if (off >= a.seg_bytes) continue;  // ragged last chunk of a segment
     vec16* in_pool = reinterpret_cast<vec16*>(a.pool + (u64)s * a.seg_stride + (u64)p * a.page_stride + off);
     vec16* in_host = reinterpret_cast<vec16*>(a.host + i * a.host_stride + (u64)s * a.seg_bytes + off);
-    if (kToHost)
-      *in_host = *in_pool;
-    else
+    if (kToHost) {
+      const vec16 v = *in_pool;
+      asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(in_host), "v"(v) : "memory");
+    } else {
       *in_pool = *in_host;
+    }
   }
 }
 
