@@ -465,6 +465,32 @@ def survey_config(torch, aibx, cfg, layout=None):
     hit = torch.empty(Rs, dtype=torch.int32, device="cuda")
     ms_r, _ = time_calls(torch, lambda: aibx.aibx_route(pod_sets, d_bo, Rs, Ns, 8, load, 1, 2, pod, hit), 10)
     out["route"] = {"requests": Rs, "us": ms_r * 1e3, "Mrequests_per_s": Rs / ms_r / 1e3}
+    # turnover, then compaction: evict fillers and insert fresh keys in rounds of 65,536 (a third of
+    # the table's keys at most), look at the tombstones left behind, rebuild into a second table
+    q = 1 << 16
+    rounds = min(64, n_fill // (3 * q))
+    if rounds > 0:
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(cfg)
+        ev = torch.empty(q, dtype=torch.int64, device="cuda")
+        for r in range(rounds):
+            fresh = torch.randint(1, 2**62, (q,), dtype=torch.int64, device="cuda", generator=gen)
+            aibx.aibx_index_evict(ix, fk[r * q:(r + 1) * q], q, ev, c[3:5])
+            aibx.aibx_index_insert(ix, fresh, fresh, q, c[0:3])
+        st = torch.zeros(2, dtype=torch.int64, device="cuda")
+        aibx.aibx_index_stats(ix, st)
+        live, tombs = st.tolist()
+        ms_before, _ = time_calls(torch, lambda: aibx.aibx_prefix_match(ix, h, d_bo, Rs, Ns, v, m), 10)
+        storage2 = torch.empty(aibx.aibx_index_storage_bytes(wl.n_slots), dtype=torch.uint8, device="cuda")
+        ix2 = aibx.aibx_index_create(storage2, wl.n_slots)
+        ms_rb, _ = time_calls(torch, lambda: aibx.aibx_index_rebuild(ix, ix2), 5, warm=1)
+        aibx.aibx_index_stats(ix2, st)
+        live2, tombs2 = st.tolist()
+        ms_after, _ = time_calls(torch, lambda: aibx.aibx_prefix_match(ix2, h, d_bo, Rs, Ns, v, m), 10)
+        out["rebuild"] = {"turnover_keys": rounds * q, "live": live, "tombstones": tombs, "rebuild_ms": ms_rb,
+                          "rebuild_Mkeys_per_s": live / ms_rb / 1e3, "live_after": live2, "tombstones_after": tombs2,
+                          "scaled_match_ms_before": ms_before, "scaled_match_ms_after": ms_after}
+        aibx.aibx_index_destroy(ix2)
     aibx.aibx_index_destroy(ix)
     return out
 

@@ -13,6 +13,7 @@
  *   aibx_index_insert  metadata update: (key -> value) upsert           (Section 3.2.5)
  *   aibx_index_evict   metadata update: removal of evicted keys          (Section 3.2.5)
  *   aibx_index_touch / _age / _select_victims   scan-resistant victim selection (Section 3.2.5)
+ *   aibx_index_rebuild compaction / resize of the index into a second table   (Section 3.2.5)
  *   aibx_kv_gather     paged KV pool -> contiguous staging (offload)     (Section 3.2.5)
  *   aibx_kv_scatter    contiguous staging -> paged KV pool (onload)      (Section 3.2.5)
  *   aibx_kv_offload / aibx_kv_onload   paged KV pool <-> pinned host memory, one kernel each way
@@ -165,6 +166,24 @@ int aibx_index_select_victims(const aibx_index_t* index, uint32_t protect_count,
 
 /* *d_live_out (device uint64) = number of keys in the index. */
 int aibx_index_count(const aibx_index_t* index, uint64_t* d_live_out, void* stream);
+
+/* d_out2 (device uint64[2]) = {number of keys, number of tombstones}. Tombstones are slots whose
+ * key was evicted from a bucket with no free slot; they keep probe sequences intact, are reused by
+ * later inserts, and lengthen lookups while they last. Their number is a property of this table's
+ * history, not of its contents. */
+int aibx_index_stats(const aibx_index_t* index, uint64_t* d_out2, void* stream);
+
+/* Rebuild (the metadata side of the pool's lifecycle, Section 3.2.5): dst is cleared and receives
+ * every (key, value) of src together with its usage word (touch count, last epoch); src is only
+ * read. With equal capacities this is a compaction - dst has no tombstones and every key sits in
+ * the first bucket of its probe sequence that had room; with different capacities it is a resize.
+ * d_counters3 (nullable, device uint64[3]) accumulates {moved, 0, dropped}: keys are dropped only
+ * when dst has fewer slots than src has keys (which ones is unspecified).
+ *   src, dst: two handles over disjoint storage. dst answers lookups once the call has completed
+ *   in stream order; the caller then swaps the handles and may destroy or reuse src.
+ * Errors: INVALID_ARG (also src == dst), ALIGN, HIP. */
+int aibx_index_rebuild(const aibx_index_t* src, aibx_index_t* dst, uint64_t* d_counters3,
+                       void* stream);
 
 /* Writes the live (key, value) pairs, in no particular order, to d_keys_out/d_values_out (each
  * uint64[capacity]) and the number of live keys to *d_n_out (device uint64; the caller zeroes

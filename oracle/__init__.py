@@ -63,6 +63,7 @@ def _load():
             f.argtypes = [C.POINTER(_PoolDesc), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
                           C.c_uint64, C.c_void_p]
         lib.orc_index_touch.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_uint32]
+        lib.orc_index_rebuild.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         lib.orc_index_age.argtypes = [C.c_void_p]
         lib.orc_index_age.restype = None
         lib.orc_index_select_victims.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p,
@@ -161,6 +162,13 @@ class Index:
         m = self._lib.orc_index_dump(self._h, _ptr(k), _ptr(v), n)
         assert m == n
         return k, v
+
+    def rebuild_into(self, dst: "Index") -> np.ndarray:
+        """dst <- this index's keys, values and usage; returns {moved, 0, dropped}."""
+        c = np.zeros(3, dtype=np.uint64)
+        rc = self._lib.orc_index_rebuild(self._h, dst._h, _ptr(c))
+        assert rc == 0
+        return c
 
     def touch(self, keys, epoch: int):
         keys = _arr(keys, np.uint64)

@@ -216,6 +216,31 @@ u64 orc_index_select_victims(const void* h, uint32_t protect_count, uint32_t bef
 
 u64 orc_index_count(const void* h) { return static_cast<const Index*>(h)->map.size(); }
 
+// Rebuild into a second index (compaction or resize of the pool's metadata, Section 3.2.5).
+// reading: dst is emptied and then holds exactly src's keys with their values and usage; src is
+// unchanged. Only when dst's capacity is below src's key count are keys left out - `capacity` of
+// them move, the others are dropped, and which ones is not specified (here: ascending key order).
+// counters3 accumulates {moved, 0, dropped}.
+int orc_index_rebuild(const void* src_h, void* dst_h, u64* counters3) {
+  if (!src_h || !dst_h || src_h == dst_h) return -1;
+  const Index* src = static_cast<const Index*>(src_h);
+  Index* dst = static_cast<Index*>(dst_h);
+  dst->map.clear();
+  dst->usage.clear();
+  std::vector<u64> keys;
+  for (const auto& kv : src->map) keys.push_back(kv.first);
+  std::sort(keys.begin(), keys.end());
+  u64 moved = 0, dropped = 0;
+  for (u64 k : keys) {
+    if (dst->map.size() >= dst->capacity) { ++dropped; continue; }
+    dst->map.emplace(k, src->map.at(k));
+    dst->usage[k] = src->usage.at(k);
+    ++moved;
+  }
+  if (counters3) { counters3[0] += moved; counters3[2] += dropped; }
+  return 0;
+}
+
 // Writes up to `capacity` (key, value) pairs in ascending key order; returns the number of live
 // keys (which may exceed `capacity`).
 u64 orc_index_dump(const void* h, u64* keys_out, u64* values_out, u64 capacity) {

@@ -6,6 +6,7 @@ from .binding import (AibxError, PoolDesc, AIBX_NO_VALUE, aibx_version, aibx_has
                       aibx_block_hash, aibx_index_storage_bytes, aibx_index_create,
                       aibx_index_destroy, aibx_index_clear, aibx_index_insert, aibx_index_evict,
                       aibx_index_count, aibx_index_dump, aibx_index_touch, aibx_index_age,
-                      aibx_index_select_victims, aibx_prefix_match, aibx_hash_match, aibx_route,
+                      aibx_index_select_victims, aibx_index_stats, aibx_index_rebuild, aibx_prefix_match,
+                      aibx_hash_match, aibx_route,
                       make_pool_desc,
                       aibx_kv_gather, aibx_kv_scatter, aibx_kv_offload, aibx_kv_onload)

@@ -17,6 +17,7 @@ EXPORTS = [
     "aibx_block_hash", "aibx_index_storage_bytes", "aibx_index_create", "aibx_index_destroy",
     "aibx_index_clear", "aibx_index_insert", "aibx_index_evict", "aibx_index_count",
     "aibx_index_dump", "aibx_index_touch", "aibx_index_age", "aibx_index_select_victims",
+    "aibx_index_stats", "aibx_index_rebuild",
     "aibx_prefix_match", "aibx_hash_match", "aibx_route", "aibx_kv_gather", "aibx_kv_scatter", "aibx_kv_offload", "aibx_kv_onload",
 ]
 
@@ -65,6 +66,8 @@ def load(build_if_missing: bool = True):
     lib.aibx_index_evict.argtypes = [vp, vp, i64, vp, vp, vp]
     lib.aibx_index_count.argtypes = [vp, vp, vp]
     lib.aibx_index_dump.argtypes = [vp, vp, vp, u64, vp, vp]
+    lib.aibx_index_stats.argtypes = [vp, vp, vp]
+    lib.aibx_index_rebuild.argtypes = [vp, vp, vp, vp]
     lib.aibx_prefix_match.argtypes = [vp, vp, vp, i32, i64, vp, vp, vp]
     lib.aibx_index_touch.argtypes = [vp, vp, i64, C.c_uint32, vp]
     lib.aibx_index_age.argtypes = [vp, vp]
@@ -159,6 +162,14 @@ def aibx_index_evict(index, d_keys, n, d_values_out=None, d_counters2=None, stre
 
 def aibx_index_count(index, d_live_out, stream=None):
     _check("aibx_index_count", load().aibx_index_count(index, _p(d_live_out, U64), _s(stream)))
+
+
+def aibx_index_stats(index, d_out2, stream=None):
+    _check("aibx_index_stats", load().aibx_index_stats(index, _p(d_out2, U64), _s(stream)))
+
+
+def aibx_index_rebuild(src, dst, d_counters3=None, stream=None):
+    _check("aibx_index_rebuild", load().aibx_index_rebuild(src, dst, _p(d_counters3, U64), _s(stream)))
 
 
 def aibx_index_dump(index, d_keys_out, d_values_out, capacity, d_n_out, stream=None):

@@ -95,14 +95,43 @@ __device__ __forceinline__ u32 group_sum(u32 v) {
   return total;
 }
 
-__global__ __launch_bounds__(kIndexThreads) void index_insert_kernel(
-    Table t, const u64* __restrict__ keys, const u64* __restrict__ values, int64_t n,
-    u64* __restrict__ counters3) {
+// Where the (key, value) pairs of an insert come from: a batch handed in by the caller, or the
+// live slots of another table (rebuild), which also bring their usage word along.
+struct BatchSource {
+  const u64* __restrict__ keys;
+  const u64* __restrict__ values;
+  int64_t n;
+  __device__ __forceinline__ bool get(int64_t i, u64& key, u64& val, u32& use) const {
+    key = keys[i];
+    val = values[i];
+    use = 0;  // a new key starts untouched
+    return true;
+  }
+};
+struct TableSource {
+  const u64* __restrict__ slots;
+  const u32* __restrict__ usage;
+  int64_t n;  // slots of the source table
+  __device__ __forceinline__ bool get(int64_t i, u64& key, u64& val, u32& use) const {
+    const u64 w = key_word_of_slot((u64)i);
+    key = slots[w];
+    if (key == kEmpty || key == kTomb) return false;  // nothing stored here
+    val = slots[w + kBucket];
+    use = usage[i];
+    return true;
+  }
+};
+
+template <class Source>
+__global__ __launch_bounds__(kIndexThreads) void index_insert_kernel(Table t, Source src,
+                                                                    u64* __restrict__ counters3) {
   u32 n_ins = 0, n_upd = 0, n_full = 0;
   const u64 n_buckets = t.bucket_mask + 1;
+  const int64_t n = src.n;
   for (int64_t i = (int64_t)blockIdx.x * kIndexThreads + threadIdx.x; i < n; i += (int64_t)gridDim.x * kIndexThreads) {
-  const u64 key = keys[i];
-  const u64 val = values[i];
+  u64 key, val;
+  u32 use;
+  if (!src.get(i, key, val, use)) continue;
   bool active = key != kEmpty && key != kTomb;
   if (!active) ++n_full;  // reserved key: dropped
   const u64 step = probe_step(key);
@@ -159,7 +188,7 @@ __global__ __launch_bounds__(kIndexThreads) void index_insert_kernel(
                                 (unsigned long long)key);
       if (old == cand_expected) {  // the slot is ours
         store_value(cslot + kBucket, val);
-        t.usage[cand_bucket * kBucket + cand_slot] = 0;  // a new key starts untouched
+        t.usage[cand_bucket * kBucket + cand_slot] = use;
         ++n_ins;
         break;
       }
@@ -295,16 +324,25 @@ __global__ __launch_bounds__(kIndexThreads) void fill_zero_kernel(uint4* p, u64 
     p[i] = uint4{0, 0, 0, 0};
 }
 
-__global__ void zero_word_kernel(u64* p) { *p = 0; }
+__global__ void zero_word_kernel(u64* p, int n) {
+  for (int i = 0; i < n; ++i) p[i] = 0;
+}
 
-__global__ __launch_bounds__(kIndexThreads) void index_count_kernel(const u64* slots, u64 n_slots, u64* live_out) {
-  u32 mine = 0;
+// out2[0] += live slots; out2[1] += tombstones when want_tombstones (else out2 has one word only)
+__global__ __launch_bounds__(kIndexThreads) void index_count_kernel(const u64* slots, u64 n_slots, u64* out2,
+                                                                   bool want_tombstones) {
+  u32 live = 0, tombs = 0;
   for (u64 i = (u64)blockIdx.x * kIndexThreads + threadIdx.x; i < n_slots; i += (u64)gridDim.x * kIndexThreads) {
     const u64 k = slots[key_word_of_slot(i)];
-    mine += (k != kEmpty && k != kTomb);
+    live += (k != kEmpty && k != kTomb);
+    tombs += k == kTomb;
   }
-  const u32 total = group_sum(mine);
-  if (threadIdx.x == 0 && total) atomicAdd((unsigned long long*)live_out, (unsigned long long)total);
+  const u32 total = group_sum(live);
+  if (threadIdx.x == 0 && total) atomicAdd((unsigned long long*)out2, (unsigned long long)total);
+  if (want_tombstones) {
+    const u32 total_t = group_sum(tombs);
+    if (threadIdx.x == 0 && total_t) atomicAdd((unsigned long long*)out2 + 1, (unsigned long long)total_t);
+  }
 }
 
 // Dump and victim selection: emit the (key, value) pairs of the slots that pass a test, in no
@@ -437,8 +475,8 @@ int aibx_index_insert(aibx_index_t* index, const uint64_t* d_keys, const uint64_
   if (n == 0) return AIBX_OK;
   if (!d_keys || !d_values) return AIBX_ERR_INVALID_ARG;
   if (!aligned(d_keys, 8) || !aligned(d_values, 8) || !aligned(d_counters3, 8)) return AIBX_ERR_ALIGN;
-  index_insert_kernel<<<pass_grid((u64)n), kIndexThreads, 0, as_stream(stream)>>>(table_of(index), d_keys, d_values,
-                                                                                   n, d_counters3);
+  index_insert_kernel<<<pass_grid((u64)n), kIndexThreads, 0, as_stream(stream)>>>(
+      table_of(index), BatchSource{d_keys, d_values, n}, d_counters3);
   return launch_status();
 }
 
@@ -475,7 +513,7 @@ int aibx_index_select_victims(const aibx_index_t* index, uint32_t protect_count,
   if (capacity && (!d_keys_out || !d_values_out)) return AIBX_ERR_INVALID_ARG;
   if (!aligned(d_keys_out, 8) || !aligned(d_values_out, 8) || !aligned(d_n_out, 8)) return AIBX_ERR_ALIGN;
   hipStream_t st = as_stream(stream);
-  zero_word_kernel<<<1, 1, 0, st>>>(d_n_out);
+  zero_word_kernel<<<1, 1, 0, st>>>(d_n_out, 1);
   index_emit_kernel<<<pass_grid(index->n_slots), kIndexThreads, 0, st>>>(
       index->slots, index->usage, index->n_slots, EmitTest{true, protect_count, before_epoch}, d_keys_out,
       d_values_out, capacity, d_n_out);
@@ -486,8 +524,28 @@ int aibx_index_count(const aibx_index_t* index, uint64_t* d_live_out, void* stre
   if (!index || !d_live_out) return AIBX_ERR_INVALID_ARG;
   if (!aligned(d_live_out, 8)) return AIBX_ERR_ALIGN;
   hipStream_t st = as_stream(stream);
-  zero_word_kernel<<<1, 1, 0, st>>>(d_live_out);
-  index_count_kernel<<<pass_grid(index->n_slots), kIndexThreads, 0, st>>>(index->slots, index->n_slots, d_live_out);
+  zero_word_kernel<<<1, 1, 0, st>>>(d_live_out, 1);
+  index_count_kernel<<<pass_grid(index->n_slots), kIndexThreads, 0, st>>>(index->slots, index->n_slots, d_live_out,
+                                                                         false);
+  return launch_status();
+}
+
+int aibx_index_stats(const aibx_index_t* index, uint64_t* d_out2, void* stream) {
+  if (!index || !d_out2) return AIBX_ERR_INVALID_ARG;
+  if (!aligned(d_out2, 8)) return AIBX_ERR_ALIGN;
+  hipStream_t st = as_stream(stream);
+  zero_word_kernel<<<1, 1, 0, st>>>(d_out2, 2);
+  index_count_kernel<<<pass_grid(index->n_slots), kIndexThreads, 0, st>>>(index->slots, index->n_slots, d_out2, true);
+  return launch_status();
+}
+
+int aibx_index_rebuild(const aibx_index_t* src, aibx_index_t* dst, uint64_t* d_counters3, void* stream) {
+  if (!src || !dst || src == dst || src->slots == dst->slots) return AIBX_ERR_INVALID_ARG;
+  if (!aligned(d_counters3, 8)) return AIBX_ERR_ALIGN;
+  const int rc = aibx_index_clear(dst, stream);
+  if (rc != AIBX_OK) return rc;
+  index_insert_kernel<<<pass_grid(src->n_slots), kIndexThreads, 0, as_stream(stream)>>>(
+      table_of(dst), TableSource{src->slots, src->usage, (int64_t)src->n_slots}, d_counters3);
   return launch_status();
 }
 
@@ -497,7 +555,7 @@ int aibx_index_dump(const aibx_index_t* index, uint64_t* d_keys_out, uint64_t* d
   if (capacity && (!d_keys_out || !d_values_out)) return AIBX_ERR_INVALID_ARG;
   if (!aligned(d_keys_out, 8) || !aligned(d_values_out, 8) || !aligned(d_n_out, 8)) return AIBX_ERR_ALIGN;
   hipStream_t st = as_stream(stream);
-  zero_word_kernel<<<1, 1, 0, st>>>(d_n_out);
+  zero_word_kernel<<<1, 1, 0, st>>>(d_n_out, 1);
   index_emit_kernel<<<pass_grid(index->n_slots), kIndexThreads, 0, st>>>(
       index->slots, index->usage, index->n_slots, EmitTest{false, 0, 0}, d_keys_out, d_values_out, capacity,
       d_n_out);

@@ -132,6 +132,18 @@ class HipIndex:
         order = np.argsort(hk, kind="stable")
         return hk[order], hv[order]
 
+    def stats(self):
+        """(live keys, tombstones)"""
+        out = self.t.empty(2, dtype=self.t.int64, device="cuda")
+        self.a.aibx_index_stats(self.h, out)
+        live, tombs = out.tolist()
+        return live, tombs
+
+    def rebuild_into(self, dst: "HipIndex"):
+        c = self.t.zeros(3, dtype=self.t.int64, device="cuda")
+        self.a.aibx_index_rebuild(self.h, dst.h, c)
+        return self._host_u64(c)
+
     def touch(self, keys, epoch):
         k = self._dev(keys)
         self.a.aibx_index_touch(self.h, k, k.numel(), epoch)

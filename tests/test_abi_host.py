@@ -69,6 +69,8 @@ def test_argument_errors_are_raised_before_any_launch(lib):
     assert lib.aibx_index_destroy(None) == 0
     assert lib.aibx_index_touch(None, fake, 1, 0, None) == -1
     assert lib.aibx_index_age(None, None) == -1
+    assert lib.aibx_index_stats(None, fake, None) == -1
+    assert lib.aibx_index_rebuild(None, None, None, None) == -1
     assert lib.aibx_index_select_victims(None, 2, 5, fake, fake, 1, fake, None) == -1
     assert lib.aibx_hash_match(None, fake, fake, fake, 1, 1, 16, 0, fake, fake, fake, None) == -1
     # routing

@@ -177,6 +177,84 @@ def test_index_random_ops_against_oracle(n_slots, seed):
     assert np.array_equal(gi.counters_evict, oi.counters_evict)
 
 
+def _churn(rng, gi, oi, universe, n_slots, steps):
+    for _ in range(steps):
+        op = rng.integers(0, 5)
+        m = int(rng.integers(0, min(len(universe), n_slots // 2 + 3)))
+        k = rng.choice(universe, size=m, replace=False)
+        if op <= 1:
+            if gi.count() + m > n_slots:
+                continue
+            v = rng.integers(0, 2**40, size=m, dtype=np.uint64)
+            gi.insert(k, v)
+            oi.insert(k, v)
+        elif op == 2:
+            assert np.array_equal(gi.evict(k), oi.evict(k))
+        elif op == 3:
+            e = int(rng.integers(0, 50))
+            gi.touch(k, e)
+            oi.touch(k, e)
+        else:
+            gv, gm = gi.match(k, [0, m])
+            ov, om = oi.match(k, [0, m])
+            assert np.array_equal(gv, ov) and np.array_equal(gm, om)
+
+
+def _same_index(gi, oi):
+    for a, b in zip(gi.dump(), oi.dump()):
+        assert np.array_equal(a, b)
+    for protect, epoch in ((1, 1), (2, 25), (3, 60), (255, 1 << 20)):
+        for a, b in zip(gi.select_victims(protect, epoch), oi.select_victims(protect, epoch)):
+            assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("n_slots,seed", [(64, 0), (1024, 0), (1024, 1), (4096, 0)])
+def test_index_rebuild_compacts_and_keeps_everything(n_slots, seed):
+    """Churn on crowded probe sequences leaves tombstones behind; the rebuilt table has none, holds
+    the same keys, values and usage words as the oracle's copy, and goes on working like any index."""
+    rng = np.random.default_rng(7000 + n_slots + seed)
+    gi, oi = HipIndex(n_slots), oracle.Index(n_slots)
+    universe = np.unique(_same_bucket_keys(rng, n_slots, 3 * n_slots))
+    _churn(rng, gi, oi, universe, n_slots, 80)
+    room = n_slots - n_slots // 16 - gi.count()           # fill up, then evict from the full buckets
+    if room > 0:
+        absent = np.setdiff1d(universe, oi.dump()[0])[:room]
+        gi.insert(absent, absent >> np.uint64(5))
+        oi.insert(absent, absent >> np.uint64(5))
+    present = oi.dump()[0]
+    assert np.array_equal(gi.evict(present[::3]), oi.evict(present[::3]))
+    live, tombs = gi.stats()
+    assert live == oi.count() and tombs > 0
+    g2, o2 = HipIndex(n_slots), oracle.Index(n_slots)
+    g2.insert(np.array([12345], dtype=np.uint64), np.array([1], dtype=np.uint64))   # wiped by the rebuild
+    assert np.array_equal(gi.rebuild_into(g2), oi.rebuild_into(o2))
+    assert g2.stats() == (live, 0)
+    _same_index(g2, o2)
+    _same_index(gi, oi)                                   # the source is only read
+    assert gi.stats() == (live, tombs)
+    _churn(rng, g2, o2, universe, n_slots, 60)            # the copy is a working index
+    _same_index(g2, o2)
+    # same call as a resize: up keeps everything, down keeps as many keys as fit
+    g3, o3 = HipIndex(4 * n_slots), oracle.Index(4 * n_slots)
+    assert np.array_equal(g2.rebuild_into(g3), o2.rebuild_into(o3))
+    _same_index(g3, o3)
+    small = max(8, n_slots // 8)
+    g4, o4 = HipIndex(small), oracle.Index(small)
+    cg, co = g3.rebuild_into(g4), o3.rebuild_into(o4)
+    assert np.array_equal(cg, co) and g4.stats() == (o4.count(), 0)
+    full = dict(zip(*[x.tolist() for x in o3.dump()]))
+    gk, gv = g4.dump()
+    assert len(set(gk.tolist())) == len(gk) and all(full[a] == b for a, b in zip(gk.tolist(), gv.tolist()))
+
+
+def test_index_rebuild_rejects_itself():
+    import paper_2504_03648_amd as aibx
+    gi = HipIndex(64)
+    with pytest.raises(aibx.AibxError) as e:
+        aibx.aibx_index_rebuild(gi.h, gi.h)
+    assert e.value.status == -1
+
+
 def test_index_overflow_counts():
     """m > n_slots distinct keys into an empty table: exactly n_slots succeed, the rest are
     counted full; every survivor is found with its value."""
