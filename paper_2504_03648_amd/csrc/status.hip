@@ -18,7 +18,7 @@ int hip_failed(hipError_t e) {
 
 extern "C" {
 
-int aibx_version(void) { return 100; }
+int aibx_version(void) { return 200; }  // 0.2.0
 
 int aibx_hash_version(void) { return 1; }
 
