@@ -57,11 +57,17 @@ def test_block_hash_configs_full_size(hip, cfg):
 
 @pytest.mark.parametrize("B", [16, 32, 64])
 def test_block_hash_many_requests(hip, B):
-    """Thousands of requests take the one-wavefront-per-request launch: carry in registers,
-    several tiles per wavefront, ragged tails."""
+    """In a batch of thousands a request of up to 8 tiles (8192 tokens) is hashed by one wavefront
+    (carry in registers, ragged tails), a longer one by the four wavefronts of its workgroup
+    (carry through LDS): both sides of that boundary, and long requests of several rounds."""
     rng = np.random.default_rng(7 * B)
     tok, tok_off, lens = _ragged(rng, 5000, 0, 40 * B)
-    lens[11] = 9000 + B // 3                      # a long request among the short ones
+    lens[11] = 9000 + B // 3                      # long requests among the short ones
+    lens[12] = 8192                               # exactly 8 tiles
+    lens[13] = 8192 + B                           # one block more
+    lens[14] = 8192 - 1
+    lens[700] = 13 * 1024 + 5 * B + 3             # 14 tiles, the last one ragged
+    lens[4999] = 33 * 1024 + B                    # 34 tiles: nine rounds of four wavefronts
     np.cumsum(lens, out=tok_off[1:])
     tok = rng.integers(0, 32000, size=int(tok_off[-1]), dtype=np.int32)
     blk_off = np.zeros(len(lens) + 1, dtype=np.int64)
@@ -403,12 +409,14 @@ def test_scan_does_not_push_out_reused_blocks_full_flow():
 # ---- hash + match in one launch -------------------------------------------------------------------
 @pytest.mark.parametrize("B,n_req", [(16, 37), (32, 21), (64, 19), (16, 5000), (64, 4500), (24, 11)])
 def test_hash_match_equals_hash_then_match(B, n_req):
-    """Few requests (4 wavefronts each), thousands (1 wavefront each), and a block size that runs
-    as two launches; half of the requests are indexed, a slice of their blocks evicted again."""
+    """Few requests (4 wavefronts each), thousands (1 wavefront each, 4 for the long ones), and a
+    block size that runs as two launches; half of the requests are indexed, a slice of their blocks evicted again."""
     rng = np.random.default_rng(B * 7 + n_req)
     tok, tok_off, lens = _ragged(rng, n_req, 0, 30 * B if n_req > 1000 else 150 * B)
     lens[1] = 0
     lens[2] = B - 1
+    if n_req > 1000:                              # requests long enough to be shared by four wavefronts
+        lens[6], lens[7], lens[8] = 8192 + 3 * B, 8192 + 3 * B + 40, 21 * 1024 + 7
     np.cumsum(lens, out=tok_off[1:])
     tok = rng.integers(0, 32000, size=int(tok_off[-1]), dtype=np.int32)
     # requests come in pairs that share a prefix of the first of the two
