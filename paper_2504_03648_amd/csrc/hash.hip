@@ -2,8 +2,8 @@
 // routing, Section 3.2.2, and its cross-request KV reuse, Section 3.2.5). The definition is in
 // aibx.h; this file evaluates it on the GPU.
 //
-// Layout of the work: one workgroup of 4 wavefronts per request; short requests of a large batch
-// are left to the first of them. A
+// Layout of the work: one workgroup per request; the request is hashed by one wavefront or by
+// four together, depending on its length and on the shape of the batch (see launch_hash). A
 // wavefront takes a tile of 1024 consecutive tokens (64 coalesced tokens per load, 16 loads in
 // flight), so a lane always sees the same position-in-block and folds its position constant once
 // (request starts are only 4-byte aligned, so wider loads would need peeling). The per-block sums
@@ -22,7 +22,6 @@ constexpr u64 K2 = 0xBB67AE8584CAA73Bull;
 constexpr u64 K3 = 0x3C6EF372FE94F82Bull;
 
 constexpr int kGeneralWaves = 4;  // wavefronts per request on the general path
-constexpr int kHashWaves = 4;     // wavefronts per request on the fast path
 constexpr int kTileTokens = 1024;  // tokens per wavefront tile
 constexpr int kLoads = kTileTokens / kWave;
 
@@ -123,7 +122,7 @@ struct MatchOut {
   int32_t* match_len;
 };
 
-template <int kB, bool kMatch>
+template <int kB, int kHashWaves, bool kMatch>
 __global__ __launch_bounds__(kHashWaves* kWave) void block_hash_pow2_kernel(
     const int32_t* __restrict__ tokens, const int64_t* __restrict__ tok_off,
     const int64_t* __restrict__ blk_off, u64 seed, u64* __restrict__ hash_out, MatchOut mo, int solo_tiles) {
@@ -134,21 +133,8 @@ __global__ __launch_bounds__(kHashWaves* kWave) void block_hash_pow2_kernel(
   __shared__ u64 lds_aggr[2][kHashWaves];
   __shared__ int lds_first[kHashWaves];
 
-  const int r = blockIdx.x;
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
-  const int64_t t0 = tok_off[r];
-  const int64_t b0 = blk_off[r];
-  const int64_t n_r = blk_off[r + 1] - b0;
-  if (n_r <= 0) {
-    if (kMatch && threadIdx.x == 0) mo.match_len[r] = 0;
-    return;
-  }
-  int64_t first_miss = n_r;
-  const int64_t n_tok = n_r * kB;  // tokens that belong to full blocks
-  const int32_t* tok = tokens + t0;
-  u64* out = hash_out + b0;
-
   const u64 pos_const = K0 * (u64)((lane & (kB - 1)) + 1);
   // K2^(pos+1), pos = lane within its row of 16: weight of the state entering the row
   constexpr int kRows = kNB >= 16 ? kNB / 16 : 1;
@@ -164,15 +150,28 @@ __global__ __launch_bounds__(kHashWaves* kWave) void block_hash_pow2_kernel(
   // lane that holds block `lane`'s sum after the butterfly
   const int src_lane = ((lane % kGroups) * kB + ((lane / kGroups) << (kLgB - 4))) & (kWave - 1);
 
-  u64 carry = fin(seed ^ K3);  // chain state before the first block of this iteration's tiles
+  // One request per workgroup. A request of at most solo_tiles tiles is hashed by wavefront 0 on
+  // its own (carry in registers, no barrier; the other wavefronts leave at once); a longer one is
+  // shared by all wavefronts (carry through LDS, one barrier per round).
+  const int r = blockIdx.x;
+  const int64_t b0 = blk_off[r];
+  const int64_t n_r = blk_off[r + 1] - b0;
   const int64_t n_tiles = (n_r + kNB - 1) / kNB;
-  // A request of at most solo_tiles tiles is left to wavefront 0 alone: the others leave at once,
-  // and no barrier or LDS hand-over is needed. Longer requests are shared by all wavefronts.
-  const bool solo = n_tiles <= solo_tiles;
+  const bool solo = kHashWaves == 1 || n_tiles <= solo_tiles;
   if (solo && wave != 0) return;
-  const int stride = solo ? 1 : kHashWaves;
+  if (n_r <= 0) {
+    if (kMatch && lane == 0) mo.match_len[r] = 0;
+    return;
+  }
   int parity = 0;
-  for (int64_t tile0 = 0; tile0 < n_tiles; tile0 += stride, parity ^= 1) {
+  int64_t first_miss = n_r;
+  const int64_t n_tok = n_r * kB;  // tokens that belong to full blocks
+  const int32_t* tok = tokens + tok_off[r];
+  u64* out = hash_out + b0;
+  u64 carry = fin(seed ^ K3);  // chain state before the first block of this round's tiles
+  const int stride = solo ? 1 : kHashWaves;
+  for (int64_t tile0 = 0; tile0 < n_tiles; tile0 += stride) {
+    if (!solo) parity ^= 1;
     const int64_t tile = solo ? tile0 : tile0 + wave;
     const int64_t tbase = tile * kTileTokens;
     u64 p[kLoads];
@@ -347,19 +346,28 @@ constexpr int kSoloTiles = 8;  // tiles of 1024 tokens
 
 template <bool kMatch>
 int launch_hash(const int32_t* d_tokens, const int64_t* d_tok_off, const int64_t* d_blk_off, int32_t n_req,
-                int32_t block_size, u64 seed, u64* d_hash_out, MatchOut mo, hipStream_t st) {
-  // Every request gets a workgroup of four wavefronts. In a batch of thousands of requests the
-  // GPU is full anyway, so a request of up to 8 tiles is hashed by one wavefront (the other three
-  // leave at once) and only the long ones, which would otherwise run on as the batch's tail, are
-  // shared by all four. In a small batch every request of more than one tile is shared.
-  // Measured on batches of 4 Mi blocks against one wavefront for every request: lognormal request
-  // lengths -15 % time (-24 % with the lookups in the same launch), uniform 4-tile requests equal,
-  // uniform 16-tile requests of 64-token blocks -7 % (+5 % with the lookups).
+                int64_t n_blocks_total, int32_t block_size, u64 seed, u64* d_hash_out, MatchOut mo, hipStream_t st) {
+  // Launch shape, from what the host knows (batch size and mean request length):
+  //  - fewer than 4,096 requests: four wavefronts per request, every request of more than one tile
+  //    shared by the four, so that a small batch finishes in few serial tiles;
+  //  - thousands of requests averaging under two tiles: one wavefront per request and nothing else
+  //    (workgroups of four with three idle wavefronts cost +50 % on 100,000 one-tile requests);
+  //  - thousands of longer requests: the GPU is full anyway, so a request of up to 8 tiles is hashed
+  //    by one wavefront of its workgroup, and only longer ones - which would otherwise run on as
+  //    the batch's tail - by the four together. Measured on 4 Mi-block batches against one
+  //    wavefront for every request: lognormal lengths -15 % time (-24 % with the lookups in the same
+  //    launch), uniform 4-tile requests equal, uniform 16-tile requests of 64-token blocks -7 % (+5 %).
+  const int64_t mean_tokens = n_blocks_total * (int64_t)block_size / n_req;
+  const bool single = n_req >= 4096 && mean_tokens < 2 * kTileTokens;
   const int solo_tiles = n_req < 4096 ? 1 : kSoloTiles;
   dim3 grid((u32)n_req);
-#define AIBX_LAUNCH_HASH(B)                                                                              \
-  block_hash_pow2_kernel<B, kMatch><<<grid, kHashWaves * kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off, seed, \
-                                                                   d_hash_out, mo, solo_tiles)
+#define AIBX_LAUNCH_HASH(B)                                                                                \
+  if (single)                                                                                              \
+    block_hash_pow2_kernel<B, 1, kMatch><<<grid, kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off, seed,     \
+                                                                 d_hash_out, mo, 0);                       \
+  else                                                                                                     \
+    block_hash_pow2_kernel<B, 4, kMatch><<<grid, 4 * kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off, seed, \
+                                                                     d_hash_out, mo, solo_tiles)
   switch (block_size) {
     case 16: AIBX_LAUNCH_HASH(16); break;
     case 32: AIBX_LAUNCH_HASH(32); break;
@@ -385,7 +393,7 @@ extern "C" int aibx_block_hash(const int32_t* d_tokens, const int64_t* d_tok_off
     return AIBX_ERR_ALIGN;
   hipStream_t st = as_stream(stream);
   if (block_size == 16 || block_size == 32 || block_size == 64)
-    return launch_hash<false>(d_tokens, d_tok_off, d_blk_off, n_req, block_size, seed, d_hash_out, MatchOut{}, st);
+    return launch_hash<false>(d_tokens, d_tok_off, d_blk_off, n_req, n_blocks_total, block_size, seed, d_hash_out, MatchOut{}, st);
   block_hash_general_kernel<<<dim3((u32)n_req), kGeneralWaves * kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off,
                                                                                block_size, seed, d_hash_out);
   return launch_status();
@@ -416,6 +424,6 @@ extern "C" int aibx_hash_match(const aibx_index_t* index, const int32_t* d_token
   mo.table = table_of(index);
   mo.values_out = d_values_out;
   mo.match_len = d_match_len;
-  return launch_hash<true>(d_tokens, d_tok_off, d_blk_off, n_req, block_size, seed, d_hash_out, mo,
+  return launch_hash<true>(d_tokens, d_tok_off, d_blk_off, n_req, n_blocks_total, block_size, seed, d_hash_out, mo,
                            as_stream(stream));
 }
