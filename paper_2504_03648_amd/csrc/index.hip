@@ -27,9 +27,13 @@ namespace {
 // lanes that refill themselves with their next key (no gain: the bound is lines requested).
 __global__ __launch_bounds__(kIndexThreads) void prefix_match_kernel(
     Table t, const u64* __restrict__ hashes, const int64_t* __restrict__ blk_off,
-    u64* __restrict__ values_out, int32_t* __restrict__ match_len) {
+    u64* __restrict__ values_out, int32_t* __restrict__ match_len, int n_req, int req_per_xcd) {
   __shared__ int lds_first[kWavesPerGroup];
-  const int r = blockIdx.x;
+  // Workgroup ids are dealt round-robin over the 8 XCDs; XCD x takes requests [x*req_per_xcd, +req_per_xcd),
+  // so that neighbouring requests - which tend to share a prefix, i.e. keys - meet in one L2
+  // (config 2, groups of 8 requests sharing half their blocks: 58 -> 77 G probes/s).
+  const int r = (int)(blockIdx.x & 7u) * req_per_xcd + (int)(blockIdx.x >> 3);
+  if (r >= n_req) return;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int64_t b0 = blk_off[r];
   const int64_t n_r = blk_off[r + 1] - b0;
@@ -570,8 +574,9 @@ int aibx_prefix_match(const aibx_index_t* index, const uint64_t* d_hashes, const
   if (!d_blk_off || !d_match_len || (n_blocks_total > 0 && !d_hashes)) return AIBX_ERR_INVALID_ARG;
   if (!aligned(d_hashes, 8) || !aligned(d_blk_off, 8) || !aligned(d_values_out, 8) || !aligned(d_match_len, 4))
     return AIBX_ERR_ALIGN;
-  prefix_match_kernel<<<(u32)n_req, kIndexThreads, 0, as_stream(stream)>>>(table_of(index), d_hashes, d_blk_off,
-                                                                           d_values_out, d_match_len);
+  const int req_per_xcd = (n_req + 7) / 8;
+  prefix_match_kernel<<<(u32)req_per_xcd * 8u, kIndexThreads, 0, as_stream(stream)>>>(
+      table_of(index), d_hashes, d_blk_off, d_values_out, d_match_len, n_req, req_per_xcd);
   return launch_status();
 }
 
