@@ -171,6 +171,10 @@ __global__ __launch_bounds__(kHashWaves* kWave) void block_hash_pow2_kernel(
   }
   int parity = 0;
   int64_t first_miss = n_r;
+  constexpr int kPack = kWave / kNB < 1 ? 1 : kWave / kNB;  // tiles per lookup round (lookups in this kernel)
+  u64 pend_h = 0;
+  int64_t pend_jb = 0;
+  bool pend_valid = false;
   const int64_t n_tok = n_r * kB;  // tokens that belong to full blocks
   const int32_t* tok = tokens + tok_off[r];
   u64* out = hash_out + b0;
@@ -267,11 +271,30 @@ __global__ __launch_bounds__(kHashWaves* kWave) void block_hash_pow2_kernel(
     for (int r = 1; r < kRows; ++r) enter = row == r ? y[r] + ipow(K2, 16 * r) * cin : enter;
     const u64 h = out_hash(row_w * enter + local);
     if (valid && (!kMatch || hash_out)) out[jb] = h;
-    if constexpr (kMatch) {
+    if constexpr (kMatch && kPack == 1) {
       const u64 v = lookup_one(mo.table, h, valid);
       if (valid && mo.values_out) mo.values_out[b0 + jb] = v;
       const u64 miss = __ballot(valid && v == kNoValue);
       if (miss && first_miss == n_r) first_miss = tile * kNB + (__ffsll((unsigned long long)miss) - 1);
+    }
+    if constexpr (kMatch && kPack > 1) {
+      // A tile of larger blocks fills only kNB of the 64 lanes. Its hashes are parked in lane group
+      // `slot` of a pending register, and the lookup runs once kPack tiles have filled every lane
+      // (or the request ends), so each lookup round trip carries 64 probes.
+      const int slot = (int)((tile0 / stride) % kPack);
+      const u64 moved = shfl64(h, lane & (kNB - 1));
+      const int64_t moved_jb = tile * kNB + (lane & (kNB - 1));
+      if (lane / kNB == slot) {
+        pend_h = moved;
+        pend_jb = moved_jb;
+        pend_valid = tile < n_tiles && moved_jb < n_r;
+      }
+      if (slot == kPack - 1 || tile0 + stride >= n_tiles) {
+        const u64 v = lookup_one(mo.table, pend_h, pend_valid);
+        if (pend_valid && mo.values_out) mo.values_out[b0 + pend_jb] = v;
+        if (pend_valid && v == kNoValue && pend_jb < first_miss) first_miss = pend_jb;
+        pend_valid = false;
+      }
     }
     if (!solo) {
       // chain state after all tiles of this iteration (only used if another iteration follows,
@@ -282,6 +305,13 @@ __global__ __launch_bounds__(kHashWaves* kWave) void block_hash_pow2_kernel(
     }
   }
   if constexpr (kMatch) {
+    if constexpr (kPack > 1) {  // first_miss was kept per lane: smallest over the wavefront
+#pragma unroll
+      for (int m = 32; m >= 1; m >>= 1) {
+        const int64_t o = (int64_t)shfl_xor64((u64)first_miss, m);
+        first_miss = o < first_miss ? o : first_miss;
+      }
+    }
     if (solo) {
       if (lane == 0) mo.match_len[r] = (int)first_miss;
     } else {
