@@ -104,6 +104,11 @@ int aibx_block_hash(const int32_t* d_tokens, const int64_t* d_tok_off, const int
  * Section 3.2.5: which blocks are cached and where). Keys are any uint64 except the two
  * reserved values; values are any uint64 except AIBX_NO_VALUE. Observable behaviour is that of
  * a map with capacity n_slots; where a key sits in the table is not observable.
+ * One bound applies to tables of more than 32,768 slots: a key is stored within the first 4,096
+ * buckets (32,768 slots) of its probe sequence or not at all, so that a table with no free slot
+ * left cannot make every absent key walk all of it. A key whose 4,096 buckets are all taken is
+ * reported `full` although slots remain elsewhere; below a load factor of 0.99 the probability of
+ * that is under 1e-18 per key.
  */
 typedef struct aibx_index aibx_index_t; /* opaque host handle */
 

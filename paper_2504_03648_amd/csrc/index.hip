@@ -144,9 +144,9 @@ __global__ __launch_bounds__(kIndexThreads) void index_insert_kernel(Table t, So
   bool have_cand = false;
   u64 cand_bucket = 0, cand_probes = 0, cand_expected = 0;
   int cand_slot = 0;
-  // Proven bound on loop trips: a scan visits at most n_buckets buckets, and a scan is repeated
+  // Proven bound on loop trips: a scan visits at most probe_limit buckets, and a scan is repeated
   // only after a lost claim, i.e. after some other insert filled a slot (at most n_slots times).
-  u64 guard = n_buckets > (1ull << 30) ? ~0ull : n_buckets * (n_buckets * kBucket + 1);
+  u64 guard = t.probe_limit * (n_buckets * kBucket + 1);  // < 2^12 * 2^37
   bool fresh = false;  // set after a lost claim
   while (active) {
     u64* bucket = bucket_words(t, b);
@@ -180,11 +180,11 @@ __global__ __launch_bounds__(kIndexThreads) void index_insert_kernel(Table t, So
       for (int j = 1; j < kBucket; ++j) cand_expected = first_free == j ? seen[j] : cand_expected;
     }
     // the probe sequence ends at a bucket with an EMPTY slot, or after every bucket was seen
-    if (!any_empty && probes + 1 < n_buckets) {
+    if (!any_empty && probes + 1 < t.probe_limit) {
       b = (b + step) & t.bucket_mask;
       ++probes;
     } else if (!have_cand) {
-      ++n_full;  // every slot of the table is taken
+      ++n_full;  // every slot the key may use is taken
       break;
     } else {
       u64* cslot = bucket_words(t, cand_bucket) + cand_slot;  // the candidate's key word
@@ -234,7 +234,6 @@ __global__ __launch_bounds__(kIndexThreads) void index_evict_kernel(
     Table t, const u64* __restrict__ keys, int64_t n, u64* __restrict__ values_out,
     u64* __restrict__ counters2) {
   u32 n_ev = 0, n_miss = 0;
-  const u64 n_buckets = t.bucket_mask + 1;
   for (int64_t i = (int64_t)blockIdx.x * kIndexThreads + threadIdx.x; i < n; i += (int64_t)gridDim.x * kIndexThreads) {
   const u64 key = keys[i];
   u64 result = kNoValue;
@@ -259,7 +258,7 @@ __global__ __launch_bounds__(kIndexThreads) void index_evict_kernel(
       if (old == key) result = slot[kBucket];  // otherwise another entry of this batch removed it first
       break;
     }
-    if (any_empty || probes + 1 >= n_buckets) break;
+    if (any_empty || probes + 1 >= t.probe_limit) break;
     b = (b + step) & t.bucket_mask;
   }
   if (values_out) values_out[i] = result;
@@ -290,7 +289,7 @@ __global__ __launch_bounds__(kIndexThreads) void index_touch_kernel(Table t, con
       u64 k[kBucket];
       load_bucket_keys(bucket_words(t, b), k);
       int hit = -1;
-      bool ends = seen_buckets >= t.bucket_mask;
+      bool ends = seen_buckets + 1 >= t.probe_limit;
 #pragma unroll
       for (int j = 0; j < kBucket; ++j) {
         if (k[j] == key) hit = j;

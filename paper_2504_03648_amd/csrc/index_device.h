@@ -27,10 +27,18 @@ constexpr int kWavesPerGroup = kIndexThreads / kWave;
 constexpr int kSlotBytes = 16, kUsageBytes = 4;  // storage per slot: the slot, then its usage word
 constexpr u32 kEpochMask = 0xFFFFFFu;             // usage word: [31:24] touch count, [23:0] last epoch
 
+// A key is stored within the first kMaxProbeBuckets buckets of its probe sequence or not at all, and
+// no lookup goes further. Below a load factor of 0.99 this never binds (a sequence of 4,096 full
+// buckets has a probability under 1e-18 even when 99 % of the buckets are full); it bounds what a
+// table with no EMPTY slot left - full, or worn down to tombstones - can cost a batch: without it
+// every absent key walks the whole table.
+constexpr u64 kMaxProbeBuckets = 4096;
+
 struct Table {
   u64* slots;
   u32* usage;
   u64 bucket_mask;
+  u64 probe_limit;  // min(n_buckets, kMaxProbeBuckets): buckets of a probe sequence that are ever used
   int shift;  // 64 - lg(n_buckets); home = (key * kHomeMul) >> shift (0 buckets bits -> 0)
 };
 
@@ -81,7 +89,7 @@ __device__ __forceinline__ u64 lookup_one(const Table& t, u64 key, bool valid) {
     const u64* bucket = bucket_words(t, b);
     u64 k[kBucket];
     load_bucket_keys(bucket, k);
-    bool ends = seen_buckets >= t.bucket_mask;  // that was the last bucket of the table
+    bool ends = seen_buckets + 1 >= t.probe_limit;  // that was the last bucket a key may be in
     int hit = -1;
 #pragma unroll
     for (int j = 0; j < kBucket; ++j) {
@@ -103,6 +111,7 @@ inline Table table_of(const aibx_index* ix) {
   t.slots = ix->slots;
   t.usage = ix->usage;
   t.bucket_mask = ix->n_buckets - 1;
+  t.probe_limit = ix->n_buckets < kMaxProbeBuckets ? ix->n_buckets : kMaxProbeBuckets;
   t.shift = 64 - ix->lg_buckets;
   return t;
 }

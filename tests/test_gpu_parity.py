@@ -183,6 +183,30 @@ def test_index_random_ops_against_oracle(n_slots, seed):
     assert np.array_equal(gi.counters_evict, oi.counters_evict)
 
 
+def test_index_beyond_full_is_bounded_and_consistent():
+    """A table larger than the probe bound, driven past its capacity: whatever was reported inserted
+    is there with its value, the rest was counted full, absent keys are reported absent (each walk
+    ends after 4,096 buckets instead of the whole table), and evicting everything empties it."""
+    n_slots = 1 << 17
+    rng = np.random.default_rng(99)
+    gi = HipIndex(n_slots)
+    keys = np.unique(rng.integers(1, 2**63, size=n_slots + 5000, dtype=np.uint64))
+    rng.shuffle(keys)
+    gi.insert(keys, keys >> np.uint64(7))
+    ins, upd, full = [int(x) for x in gi.counters_insert]
+    assert ins + full == len(keys) and upd == 0 and ins <= n_slots and ins >= int(0.999 * n_slots)
+    assert gi.stats() == (ins, 0)
+    v, _ = gi.match(keys, [0, len(keys)])
+    found = v != NO
+    assert int(found.sum()) == ins and np.array_equal(v[found], keys[found] >> np.uint64(7))
+    absent = np.setdiff1d(rng.integers(1, 2**63, size=200000, dtype=np.uint64), keys)
+    va, ma = gi.match(absent, [0, len(absent)])
+    assert np.all(va == NO) and int(ma[0]) == 0
+    out = gi.evict(keys)
+    assert np.array_equal(out[found], keys[found] >> np.uint64(7)) and np.all(out[~found] == NO)
+    assert gi.count() == 0
+
+
 def _churn(rng, gi, oi, universe, n_slots, steps):
     for _ in range(steps):
         op = rng.integers(0, 5)
