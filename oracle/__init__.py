@@ -36,6 +36,12 @@ class _PoolDesc(C.Structure):
                 ("page_stride", C.c_uint64), ("seg_bytes", C.c_uint64), ("n_pages", C.c_int64)]
 
 
+class _PoolRunsDesc(C.Structure):
+    _fields_ = [("base", C.c_void_p), ("n_seg", C.c_int32), ("n_run", C.c_int32), ("seg_stride", C.c_uint64),
+                ("page_stride", C.c_uint64), ("run_stride", C.c_uint64), ("run_bytes", C.c_uint64),
+                ("n_pages", C.c_int64)]
+
+
 _lib = None
 
 
@@ -61,6 +67,9 @@ def _load():
                                          C.c_void_p, C.c_void_p]
         for f in (lib.orc_kv_gather, lib.orc_kv_scatter):
             f.argtypes = [C.POINTER(_PoolDesc), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
+                          C.c_uint64, C.c_void_p]
+        for f in (lib.orc_kv_gather_runs, lib.orc_kv_scatter_runs):
+            f.argtypes = [C.POINTER(_PoolRunsDesc), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
                           C.c_uint64, C.c_void_p]
         lib.orc_index_touch.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_uint32]
         lib.orc_index_rebuild.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
@@ -244,3 +253,27 @@ def _copy(fn, pool, geom, page_ids, slot_ids, staging, stride):
     if rc != 0:
         raise ValueError(f"oracle copy: invalid arguments (rc={rc})")
     return int(bad[0])
+
+
+def _copy_runs(fn, pool, geom, page_ids, slot_ids, staging, stride):
+    page_ids = _arr(page_ids, np.int32)
+    slot_ids = None if slot_ids is None else _arr(slot_ids, np.int32)
+    assert pool.dtype == np.uint8 and pool.flags["C_CONTIGUOUS"]
+    assert staging.dtype == np.uint8 and staging.flags["C_CONTIGUOUS"]
+    n_seg, n_run, seg_stride, page_stride, run_stride, run_bytes, n_pages = (int(x) for x in geom)
+    d = _PoolRunsDesc(pool.ctypes.data, n_seg, n_run, seg_stride, page_stride, run_stride, run_bytes, n_pages)
+    bad = np.zeros(1, dtype=np.uint64)
+    rc = fn(C.byref(d), _ptr(page_ids), _ptr(slot_ids), len(page_ids), _ptr(staging), int(stride), _ptr(bad))
+    if rc != 0:
+        raise ValueError(f"oracle copy: invalid arguments (rc={rc})")
+    return int(bad[0])
+
+
+def kv_gather_runs(pool, geom, page_ids, slot_ids, staging, stride) -> int:
+    """pool -> staging for a pool whose segments are runs: ``geom`` = (n_seg, n_run, seg_stride,
+    page_stride, run_stride, run_bytes, n_pages). Returns the bad-page count."""
+    return _copy_runs(_load().orc_kv_gather_runs, pool, geom, page_ids, slot_ids, staging, stride)
+
+
+def kv_scatter_runs(pool, geom, page_ids, slot_ids, staging, stride) -> int:
+    return _copy_runs(_load().orc_kv_scatter_runs, pool, geom, page_ids, slot_ids, staging, stride)

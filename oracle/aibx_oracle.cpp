@@ -364,4 +364,59 @@ int orc_kv_scatter(const orc_pool_desc* pool, const int32_t* page_id, const int3
                     staging_block_stride, bad_page, false);
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same copies for a pool whose segments are not contiguous: segment s of page p is n_run runs
+// of run_bytes, run t at base + p*page_stride + s*seg_stride + t*run_stride. A token-major pool
+// ([page][token][layer]...) is the case run = one token's bytes of one layer, run_stride = one
+// token's bytes of all layers. The staging block is unchanged: segment after segment, each
+// segment's runs back to back - i.e. the copy converts between the two layouts (cross-engine
+// reuse of KV, Section 3.2.5, when the engines lay their pages out differently).
+// reading: holes and out-of-range pages as above.
+struct orc_pool_runs_desc {
+  void* base;
+  int32_t n_seg;
+  int32_t n_run;
+  u64 seg_stride;
+  u64 page_stride;
+  u64 run_stride;
+  u64 run_bytes;
+  int64_t n_pages;
+};
+
+static int copy_runs(const orc_pool_runs_desc* pool, const int32_t* page_id, const int32_t* slot_id,
+                     int64_t n, unsigned char* staging, u64 stride, u64* bad_page, bool to_staging) {
+  if (!pool || n < 0 || pool->n_seg < 1 || pool->n_run < 1) return -1;
+  const u64 seg_bytes = (u64)pool->n_run * pool->run_bytes;
+  if (stride < (u64)pool->n_seg * seg_bytes) return -1;
+  unsigned char* base = static_cast<unsigned char*>(pool->base);
+  for (int64_t i = 0; i < n; ++i) {
+    const int64_t p = page_id[i];
+    const int64_t q = slot_id ? (int64_t)slot_id[i] : i;
+    if (p < 0) continue;
+    if (p >= pool->n_pages) { if (bad_page) ++*bad_page; continue; }
+    for (int32_t s = 0; s < pool->n_seg; ++s)
+      for (int32_t t = 0; t < pool->n_run; ++t) {
+        unsigned char* in_pool = base + (u64)p * pool->page_stride + (u64)s * pool->seg_stride +
+                                 (u64)t * pool->run_stride;
+        unsigned char* in_stage = staging + (u64)q * stride + (u64)s * seg_bytes + (u64)t * pool->run_bytes;
+        if (to_staging) std::memcpy(in_stage, in_pool, pool->run_bytes);
+        else            std::memcpy(in_pool, in_stage, pool->run_bytes);
+      }
+  }
+  return 0;
+}
+
+int orc_kv_gather_runs(const orc_pool_runs_desc* pool, const int32_t* page_id, const int32_t* slot_id,
+                       int64_t n, void* staging, u64 staging_block_stride, u64* bad_page) {
+  return copy_runs(pool, page_id, slot_id, n, static_cast<unsigned char*>(staging), staging_block_stride,
+                   bad_page, true);
+}
+
+int orc_kv_scatter_runs(const orc_pool_runs_desc* pool, const int32_t* page_id, const int32_t* slot_id,
+                        int64_t n, const void* staging, u64 staging_block_stride, u64* bad_page) {
+  return copy_runs(pool, page_id, slot_id, n,
+                   const_cast<unsigned char*>(static_cast<const unsigned char*>(staging)),
+                   staging_block_stride, bad_page, false);
+}
+
 }  // extern "C"
