@@ -286,6 +286,14 @@ def survey_config(torch, aibx, cfg, layout=None):
     ms, _ = time_calls(torch, lambda: aibx.aibx_kv_scatter(desc, pa, sa, n, staging, g.blk_bytes), 7)
     out["scatter_GBps"] = traffic / ms / 1e6
     out["batch_blocks"] = n
+    if g.n_seg > 1 and g.seg_bytes % (16 * wl.block_size) == 0:
+        # the same pool bytes read as token-major pages [page][token][segment][run]: the copy converts
+        T, run = wl.block_size, g.seg_bytes // wl.block_size
+        rd = aibx.make_pool_runs_desc(pool, g.n_seg, T, run, g.blk_bytes, g.n_seg * run, run, g.n_pages)
+        ms, _ = time_calls(torch, lambda: aibx.aibx_kv_gather_runs(rd, pa, sa, n, staging, g.blk_bytes), 7)
+        out["token_major"] = {"run_bytes": run, "runs_per_segment": T, "gather_GBps": traffic / ms / 1e6}
+        ms, _ = time_calls(torch, lambda: aibx.aibx_kv_scatter_runs(rd, pa, sa, n, staging, g.blk_bytes), 7)
+        out["token_major"]["scatter_GBps"] = traffic / ms / 1e6
     # gather and scatter of disjoint pages and slots on two streams, wall time from a common start
     s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
     walls = []

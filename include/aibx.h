@@ -16,6 +16,7 @@
  *   aibx_index_rebuild compaction / resize of the index into a second table   (Section 3.2.5)
  *   aibx_kv_gather     paged KV pool -> contiguous staging (offload)     (Section 3.2.5)
  *   aibx_kv_scatter    contiguous staging -> paged KV pool (onload)      (Section 3.2.5)
+ *   aibx_kv_gather_runs / _scatter_runs  the same with a layout conversion (token-major pools)
  *   aibx_kv_offload / aibx_kv_onload   paged KV pool <-> pinned host memory, one kernel each way
  *
  * The paper prints no hash function, index layout or copy layout; the rules stated below are
@@ -279,6 +280,37 @@ int aibx_kv_gather(const aibx_pool_desc* pool, const int32_t* d_page_ids,
 int aibx_kv_scatter(const aibx_pool_desc* pool, const int32_t* d_page_ids,
                     const int32_t* d_slot_ids, int64_t n, const void* d_staging,
                     uint64_t staging_block_stride, uint64_t* d_bad_page_counter, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * The same copies for a pool whose segments are not contiguous (cross-engine reuse of KV,
+ * Section 3.2.5, between engines that lay their pages out differently). Segment s of page p is
+ * n_run runs of run_bytes; run t starts at base + p*page_stride + s*seg_stride + t*run_stride.
+ * A token-major pool [page][token][layer...] is the case run = one token's bytes of one layer:
+ * n_run = tokens per page, seg_stride = run_bytes, run_stride = n_seg*run_bytes, page_stride =
+ * n_run*n_seg*run_bytes. The staging block is as above - segment after segment, each segment's
+ * runs back to back (n_seg*n_run*run_bytes bytes) - so the copy converts between the two layouts.
+ * Everything else (holes, out-of-range pages, slot ids, strides, errors) is as for
+ * aibx_kv_gather / aibx_kv_scatter.
+ *   base 16-byte aligned; run_bytes, seg_stride, run_stride, page_stride multiples of 16, > 0
+ *   where used; n_run*run_bytes < 2^31. Runs of one page must not overlap (not checked).
+ * Errors: INVALID_ARG, ALIGN, UNSUPPORTED, HIP. */
+typedef struct {
+  void* base;           /* DEVICE pointer                         */
+  int32_t n_seg;        /* >= 1                                   */
+  int32_t n_run;        /* >= 1: runs per segment                 */
+  uint64_t seg_stride;  /* bytes between segments of one page     */
+  uint64_t page_stride; /* bytes between pages                    */
+  uint64_t run_stride;  /* bytes between runs of one segment      */
+  uint64_t run_bytes;   /* contiguous bytes per run               */
+  int64_t n_pages;      /* >= 0                                   */
+} aibx_pool_runs_desc;
+
+int aibx_kv_gather_runs(const aibx_pool_runs_desc* pool, const int32_t* d_page_ids,
+                        const int32_t* d_slot_ids, int64_t n, void* d_staging,
+                        uint64_t staging_block_stride, uint64_t* d_bad_page_counter, void* stream);
+int aibx_kv_scatter_runs(const aibx_pool_runs_desc* pool, const int32_t* d_page_ids,
+                         const int32_t* d_slot_ids, int64_t n, const void* d_staging,
+                         uint64_t staging_block_stride, uint64_t* d_bad_page_counter, void* stream);
 
 /* ------------------------------------------------------------------------------------------
  * Host-tier leg: paged pool <-> pinned host memory, moved by one kernel that addresses the host

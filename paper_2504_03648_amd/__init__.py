@@ -2,7 +2,8 @@
 (block hashing, prefix match against a GPU-resident index, index insert/evict, paged-KV
 gather/scatter). See include/aibx.h for the C ABI; `binding` mirrors it one to one."""
 from . import binding
-from .binding import (AibxError, PoolDesc, AIBX_NO_VALUE, aibx_version, aibx_hash_version,
+from .binding import (AibxError, PoolDesc, PoolRunsDesc, make_pool_runs_desc, aibx_kv_gather_runs,
+                      aibx_kv_scatter_runs, AIBX_NO_VALUE, aibx_version, aibx_hash_version,
                       aibx_block_hash, aibx_index_storage_bytes, aibx_index_create,
                       aibx_index_destroy, aibx_index_clear, aibx_index_insert, aibx_index_evict,
                       aibx_index_count, aibx_index_dump, aibx_index_touch, aibx_index_age,

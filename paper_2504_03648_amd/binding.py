@@ -18,7 +18,7 @@ EXPORTS = [
     "aibx_index_clear", "aibx_index_insert", "aibx_index_evict", "aibx_index_count",
     "aibx_index_dump", "aibx_index_touch", "aibx_index_age", "aibx_index_select_victims",
     "aibx_index_stats", "aibx_index_rebuild",
-    "aibx_prefix_match", "aibx_hash_match", "aibx_route", "aibx_kv_gather", "aibx_kv_scatter", "aibx_kv_offload", "aibx_kv_onload",
+    "aibx_prefix_match", "aibx_hash_match", "aibx_route", "aibx_kv_gather", "aibx_kv_scatter", "aibx_kv_gather_runs", "aibx_kv_scatter_runs", "aibx_kv_offload", "aibx_kv_onload",
 ]
 
 
@@ -30,6 +30,13 @@ class AibxError(RuntimeError):
             msg += ": " + lib.aibx_last_hip_error().decode()
         super().__init__(f"{fn} failed with status {status} ({msg})")
         self.status = status
+
+
+class PoolRunsDesc(C.Structure):
+    """aibx_pool_runs_desc"""
+    _fields_ = [("base", C.c_void_p), ("n_seg", C.c_int32), ("n_run", C.c_int32), ("seg_stride", C.c_uint64),
+                ("page_stride", C.c_uint64), ("run_stride", C.c_uint64), ("run_bytes", C.c_uint64),
+                ("n_pages", C.c_int64)]
 
 
 class PoolDesc(C.Structure):
@@ -76,6 +83,8 @@ def load(build_if_missing: bool = True):
     lib.aibx_hash_match.argtypes = [vp, vp, vp, vp, i32, i64, i32, u64, vp, vp, vp, vp]
     for f in (lib.aibx_kv_gather, lib.aibx_kv_scatter):
         f.argtypes = [C.POINTER(PoolDesc), vp, vp, i64, vp, u64, vp, vp]
+    for f in (lib.aibx_kv_gather_runs, lib.aibx_kv_scatter_runs):
+        f.argtypes = [C.POINTER(PoolRunsDesc), vp, vp, i64, vp, u64, vp, vp]
     for f in (lib.aibx_kv_offload, lib.aibx_kv_onload):
         f.argtypes = [C.POINTER(PoolDesc), vp, i64, vp, u64, vp, vp]
     for name in EXPORTS[4:]:
@@ -231,6 +240,25 @@ def aibx_kv_gather(pool: PoolDesc, d_page_ids, d_slot_ids, n, d_staging, staging
 def aibx_kv_scatter(pool: PoolDesc, d_page_ids, d_slot_ids, n, d_staging, staging_block_stride,
                     d_bad_page_counter=None, stream=None):
     _check("aibx_kv_scatter", load().aibx_kv_scatter(
+        C.byref(pool), _p(d_page_ids, torch.int32), _p(d_slot_ids, torch.int32), int(n),
+        _p(d_staging), int(staging_block_stride), _p(d_bad_page_counter, U64), _s(stream)))
+
+
+def make_pool_runs_desc(pool_tensor, n_seg, n_run, seg_stride, page_stride, run_stride, run_bytes, n_pages):
+    return PoolRunsDesc(pool_tensor.data_ptr(), int(n_seg), int(n_run), int(seg_stride), int(page_stride),
+                        int(run_stride), int(run_bytes), int(n_pages))
+
+
+def aibx_kv_gather_runs(pool: PoolRunsDesc, d_page_ids, d_slot_ids, n, d_staging, staging_block_stride,
+                        d_bad_page_counter=None, stream=None):
+    _check("aibx_kv_gather_runs", load().aibx_kv_gather_runs(
+        C.byref(pool), _p(d_page_ids, torch.int32), _p(d_slot_ids, torch.int32), int(n),
+        _p(d_staging), int(staging_block_stride), _p(d_bad_page_counter, U64), _s(stream)))
+
+
+def aibx_kv_scatter_runs(pool: PoolRunsDesc, d_page_ids, d_slot_ids, n, d_staging, staging_block_stride,
+                         d_bad_page_counter=None, stream=None):
+    _check("aibx_kv_scatter_runs", load().aibx_kv_scatter_runs(
         C.byref(pool), _p(d_page_ids, torch.int32), _p(d_slot_ids, torch.int32), int(n),
         _p(d_staging), int(staging_block_stride), _p(d_bad_page_counter, U64), _s(stream)))
 

@@ -97,6 +97,18 @@ def test_argument_errors_are_raised_before_any_launch(lib):
         assert f(C.byref(d), fake, 1, fake, 8200, None, None) == -2
         # an address that is not pinned host memory is refused before any launch
         assert f(C.byref(d), fake, 1, fake, 8192, None, None) == -1
+    from paper_2504_03648_amd.binding import PoolRunsDesc
+    rd = PoolRunsDesc(0x1000, 4, 16, 2048, 16 * 4 * 2048, 4 * 2048, 2048, 8)      # token-major, 128 KiB pages
+    for f in (lib.aibx_kv_gather_runs, lib.aibx_kv_scatter_runs):
+        assert f(C.byref(rd), fake, None, -1, fake, 1 << 17, None, None) == -1
+        assert f(C.byref(rd), fake, None, 0, fake, 1 << 17, None, None) == 0
+        assert f(None, fake, None, 1, fake, 1 << 17, None, None) == -1
+        assert f(C.byref(rd), fake, None, 1, fake, (1 << 17) - 16, None, None) == -1   # stride < block
+        assert f(C.byref(rd), fake, None, 1, odd, 1 << 17, None, None) == -2
+        assert f(C.byref(PoolRunsDesc(0x1000, 4, 0, 2048, 1 << 17, 8192, 2048, 8)), fake, None, 1, fake, 1 << 17, None, None) == -1
+        assert f(C.byref(PoolRunsDesc(0x1000, 4, 16, 2048, 1 << 17, 8192, 2040, 8)), fake, None, 1, fake, 1 << 17, None, None) == -2
+        assert f(C.byref(PoolRunsDesc(0x1000, 4, 16, 2048, 1 << 17, 1024, 2048, 8)), fake, None, 1, fake, 1 << 17, None, None) == -1  # runs overlap
+        assert f(C.byref(PoolRunsDesc(0x1000, 1, 1 << 20, 4096, 1 << 32, 4096, 4096, 8)), fake, None, 1, fake, 1 << 32, None, None) == -3  # segment of 4 GiB
     bad = PoolDesc(0x1000, 2, 1 << 20, 4096, 4100, 16)
     assert lib.aibx_kv_gather(C.byref(bad), fake, None, 1, fake, 8208, None, None) == -1  # page_stride < seg
     bad = PoolDesc(0x1000, 2, 1 << 20, 4112, 4104, 16)

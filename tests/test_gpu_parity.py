@@ -547,6 +547,65 @@ def test_gather_then_scatter_is_identity_on_the_pool():
     assert hb.t.equal(hb.pool, keep)
 
 
+# ---- copies with a layout conversion ---------------------------------------------------------------
+def _token_major(S, T, run, n_pages):
+    return (S, T, run, T * S * run, S * run, run, n_pages)
+
+
+@pytest.mark.parametrize("S,T,run,n_pages,n,pad", [
+    (64, 16, 2048, 40, 23, 0),        # config-2 page seen token-major: runs of one token's K or V heads
+    (61, 64, 1152, 9, 7, 0),          # MLA latent + rope key per token
+    (64, 16, 1024, 30, 30, 64),       # fp8 bytes, padded staging blocks
+    (3, 5, 16, 50, 33, 0), (1, 7, 48, 12, 12, 16), (2, 300, 4096 + 16, 6, 5, 0)])
+def test_gather_scatter_runs_parity(S, T, run, n_pages, n, pad):
+    import torch
+    import paper_2504_03648_amd as aibx
+    g = _token_major(S, T, run, n_pages)
+    blk = S * T * run
+    stride = blk + pad
+    rng = np.random.default_rng(S * 100 + T)
+    host_pool = rng.integers(0, 256, size=n_pages * blk, dtype=np.uint8)
+    pool = torch.from_numpy(host_pool.copy()).cuda()
+    desc = aibx.make_pool_runs_desc(pool, *g)
+    ids = rng.permutation(n_pages)[:n].astype(np.int32)
+    slots = rng.permutation(n).astype(np.int32)
+    if n > 4:
+        ids[1], ids[3] = -1, n_pages
+    d_ids, d_slots = torch.from_numpy(ids).cuda(), torch.from_numpy(slots).cuda()
+    bad = torch.zeros(1, dtype=torch.int64, device="cuda")
+    staging = torch.full((n * stride,), 0x5A, dtype=torch.uint8, device="cuda")
+    aibx.aibx_kv_gather_runs(desc, d_ids, d_slots, n, staging, stride, bad)
+    want = np.full(n * stride, 0x5A, dtype=np.uint8)
+    n_bad = oracle.kv_gather_runs(host_pool, g, ids, slots, want, stride)
+    assert np.array_equal(staging.cpu().numpy(), want) and int(bad.item()) == n_bad
+    # scatter other bytes back through the same list
+    fresh = rng.integers(0, 256, size=n * stride, dtype=np.uint8)
+    staging.copy_(torch.from_numpy(fresh).cuda())
+    aibx.aibx_kv_scatter_runs(desc, d_ids, d_slots, n, staging, stride, bad)
+    n_bad += oracle.kv_scatter_runs(host_pool, g, ids, slots, fresh, stride)
+    assert np.array_equal(pool.cpu().numpy(), host_pool) and int(bad.item()) == n_bad
+    # without slot ids
+    aibx.aibx_kv_gather_runs(desc, d_ids, None, n, staging, stride, None)
+    oracle.kv_gather_runs(host_pool, g, ids, None, fresh, stride)
+    assert np.array_equal(staging.cpu().numpy(), fresh)
+
+
+def test_one_run_per_segment_equals_the_plain_copy():
+    import torch
+    import paper_2504_03648_amd as aibx
+    g = Geometry(8, 32768, 60)
+    hb = HipBackend()
+    hb.pool_create(g, "bf16", 3)
+    ids = torch.from_numpy(np.random.default_rng(4).permutation(60)[:41].astype(np.int32)).cuda()
+    a = torch.zeros(41 * g.blk_bytes, dtype=torch.uint8, device="cuda")
+    b = torch.zeros_like(a)
+    aibx.aibx_kv_gather(hb.desc, ids, None, 41, a, g.blk_bytes)
+    n_seg, seg_stride, page_stride, seg_bytes, n_pages = g.as_tuple()
+    rd = aibx.make_pool_runs_desc(hb.pool, n_seg, 1, seg_stride, page_stride, 0, seg_bytes, n_pages)
+    aibx.aibx_kv_gather_runs(rd, ids, None, 41, b, g.blk_bytes)
+    assert torch.equal(a, b) and bool(a.any())
+
+
 # ---- host tier ----------------------------------------------------------------------------------
 @pytest.mark.parametrize("n_seg,seg_bytes,n,pad", [(6, 4096, 77, 0), (1, 65536, 40, 0), (64, 32768, 50, 0),
                                                    (3, 48, 33, 32), (2, 4096 + 16, 600, 16)])
