@@ -122,3 +122,43 @@ def test_copy_full_size_sampled(cfg, layout):
     assert torch.equal(_plane_sums(torch, pool, g), sums0)            # scatter(gather) = identity
     del pool, staging, planes, st2
     _free()
+
+
+def test_converting_copy_full_size_sampled():
+    """Config 2's pool read as token-major pages, at the batch size bench.py --survey times: sampled
+    blocks against the oracle, a checksum that every staged block is a permutation-free image of its
+    page, and the scatter back restores the pool."""
+    import torch
+    import paper_2504_03648_amd as aibx
+    wl = make_workload(2, "full")
+    g = wl.geom
+    S, T = g.n_seg, wl.block_size
+    run = g.seg_bytes // T
+    n = wl.batch_pages
+    pool = torch.empty(g.pool_bytes, dtype=torch.uint8, device="cuda")
+    fill_pool_torch(pool, wl.kv_dtype, 2)
+    geom = (S, T, run, g.blk_bytes, S * run, run, g.n_pages)
+    rd = aibx.make_pool_runs_desc(pool, *geom)
+    rng = np.random.default_rng(321)
+    pages = rng.permutation(g.n_pages)[:n].astype(np.int32)
+    d_pages = torch.from_numpy(pages).cuda()
+    staging = torch.full((n * g.blk_bytes,), 0x5A, dtype=torch.uint8, device="cuda")
+    aibx.aibx_kv_gather_runs(rd, d_pages, None, n, staging, g.blk_bytes)
+    torch.cuda.synchronize()
+    by_page = pool.view(g.n_pages, g.blk_bytes)
+    sample = np.unique(np.concatenate([[0, n - 1], rng.integers(0, n, size=16)]))
+    host_pool = by_page[torch.from_numpy(pages[sample].astype(np.int64)).cuda()].cpu().numpy().reshape(-1)
+    cgeom = (S, T, run, g.blk_bytes, S * run, run, len(sample))
+    want = np.zeros(len(sample) * g.blk_bytes, dtype=np.uint8)
+    assert oracle.kv_gather_runs(host_pool, cgeom, np.arange(len(sample), dtype=np.int32), None, want, g.blk_bytes) == 0
+    got = staging.view(n, g.blk_bytes)[torch.from_numpy(sample.astype(np.int64)).cuda()].cpu().numpy().reshape(-1)
+    assert np.array_equal(got, want)
+    # every block: the staged bytes are the page's bytes in another order (equal 64-bit word sums)
+    sums_pool = by_page.view(torch.int64).view(g.n_pages, -1).sum(dim=1)[d_pages.long()]
+    sums_stage = staging.view(torch.int64).view(n, -1).sum(dim=1)
+    assert torch.equal(sums_pool, sums_stage)
+    keep = by_page[d_pages.long()].clone()
+    by_page[d_pages.long()] = 0
+    aibx.aibx_kv_scatter_runs(rd, d_pages, None, n, staging, g.blk_bytes)
+    torch.cuda.synchronize()
+    assert torch.equal(by_page[d_pages.long()], keep)
