@@ -125,7 +125,7 @@ struct MatchOut {
 template <int kB, int kHashWaves, bool kMatch>
 __global__ __launch_bounds__(kHashWaves* kWave) void block_hash_pow2_kernel(
     const int32_t* __restrict__ tokens, const int64_t* __restrict__ tok_off,
-    const int64_t* __restrict__ blk_off, int n_req, int req_per_xcd, u64 seed, u64* __restrict__ hash_out,
+    const int64_t* __restrict__ blk_off, int n_req, int lg_run, u64 seed, u64* __restrict__ hash_out,
     MatchOut mo, int solo_tiles) {
   static_assert(kB == 16 || kB == 32 || kB == 64, "block size");
   constexpr int kNB = kTileTokens / kB;   // blocks per tile
@@ -154,11 +154,10 @@ __global__ __launch_bounds__(kHashWaves* kWave) void block_hash_pow2_kernel(
   // One request per workgroup. A request of at most solo_tiles tiles is hashed by wavefront 0 on
   // its own (carry in registers, no barrier; the other wavefronts leave at once); a longer one is
   // shared by all wavefronts (carry through LDS, one barrier per round).
-  // Workgroup ids are dealt round-robin over the 8 XCDs. With the lookups in this kernel XCD x takes
-  // requests [x*req_per_xcd, +req_per_xcd), so that neighbouring requests - which tend to share a
-  // prefix, i.e. index keys - meet in one L2 (config 2: -6 % time). Hashing alone streams the tokens
-  // faster with neighbouring requests on different XCDs (the contiguous map costs it 8 %).
-  const int r = kMatch ? (int)(blockIdx.x & 7u) * req_per_xcd + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+  // With the lookups in this kernel the requests are dealt to the XCDs in runs (see
+  // request_of_workgroup; config 2: -6 % time). Hashing alone streams the tokens faster with
+  // neighbouring requests on different XCDs (a contiguous map costs it 8 %).
+  const int r = kMatch ? request_of_workgroup(blockIdx.x, lg_run) : (int)blockIdx.x;
   if (r >= n_req) return;
   const int64_t b0 = blk_off[r];
   const int64_t n_r = blk_off[r + 1] - b0;
@@ -396,15 +395,15 @@ int launch_hash(const int32_t* d_tokens, const int64_t* d_tok_off, const int64_t
   const int64_t mean_tokens = n_blocks_total * (int64_t)block_size / n_req;
   const bool single = n_req >= 4096 && mean_tokens < 2 * kTileTokens;
   const int solo_tiles = n_req < 4096 ? 1 : kSoloTiles;
-  const int req_per_xcd = (n_req + 7) / 8;
-  dim3 grid((u32)req_per_xcd * 8u);
+  const int lg_run = request_run_lg(n_req);
+  dim3 grid(kMatch ? workgroups_for_requests(n_req, lg_run) : (unsigned)n_req);
 #define AIBX_LAUNCH_HASH(B)                                                                                 \
   if (single)                                                                                               \
     block_hash_pow2_kernel<B, 1, kMatch><<<grid, kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off, n_req,     \
-                                                                 req_per_xcd, seed, d_hash_out, mo, 0);     \
+                                                                 lg_run, seed, d_hash_out, mo, 0);          \
   else                                                                                                      \
     block_hash_pow2_kernel<B, 4, kMatch><<<grid, 4 * kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off, n_req, \
-                                                                     req_per_xcd, seed, d_hash_out, mo, solo_tiles)
+                                                                     lg_run, seed, d_hash_out, mo, solo_tiles)
   switch (block_size) {
     case 16: AIBX_LAUNCH_HASH(16); break;
     case 32: AIBX_LAUNCH_HASH(32); break;

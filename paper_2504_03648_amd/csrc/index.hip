@@ -27,12 +27,11 @@ namespace {
 // lanes that refill themselves with their next key (no gain: the bound is lines requested).
 __global__ __launch_bounds__(kIndexThreads) void prefix_match_kernel(
     Table t, const u64* __restrict__ hashes, const int64_t* __restrict__ blk_off,
-    u64* __restrict__ values_out, int32_t* __restrict__ match_len, int n_req, int req_per_xcd) {
+    u64* __restrict__ values_out, int32_t* __restrict__ match_len, int n_req, int lg_run) {
   __shared__ int lds_first[kWavesPerGroup];
-  // Workgroup ids are dealt round-robin over the 8 XCDs; XCD x takes requests [x*req_per_xcd, +req_per_xcd),
-  // so that neighbouring requests - which tend to share a prefix, i.e. keys - meet in one L2
-  // (config 2, groups of 8 requests sharing half their blocks: 58 -> 77 G probes/s).
-  const int r = (int)(blockIdx.x & 7u) * req_per_xcd + (int)(blockIdx.x >> 3);
+  // (config 2, groups of 8 neighbouring requests sharing half their blocks: 58 -> 77 G probes/s
+  // against request = workgroup id)
+  const int r = request_of_workgroup(blockIdx.x, lg_run);
   if (r >= n_req) return;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int64_t b0 = blk_off[r];
@@ -573,9 +572,9 @@ int aibx_prefix_match(const aibx_index_t* index, const uint64_t* d_hashes, const
   if (!d_blk_off || !d_match_len || (n_blocks_total > 0 && !d_hashes)) return AIBX_ERR_INVALID_ARG;
   if (!aligned(d_hashes, 8) || !aligned(d_blk_off, 8) || !aligned(d_values_out, 8) || !aligned(d_match_len, 4))
     return AIBX_ERR_ALIGN;
-  const int req_per_xcd = (n_req + 7) / 8;
-  prefix_match_kernel<<<(u32)req_per_xcd * 8u, kIndexThreads, 0, as_stream(stream)>>>(
-      table_of(index), d_hashes, d_blk_off, d_values_out, d_match_len, n_req, req_per_xcd);
+  const int lg_run = request_run_lg(n_req);
+  prefix_match_kernel<<<workgroups_for_requests(n_req, lg_run), kIndexThreads, 0, as_stream(stream)>>>(
+      table_of(index), d_hashes, d_blk_off, d_values_out, d_match_len, n_req, lg_run);
   return launch_status();
 }
 

@@ -106,6 +106,27 @@ __device__ __forceinline__ u64 lookup_one(const Table& t, u64 key, bool valid) {
   return result;
 }
 
+// Request -> workgroup map of the kernels that probe the index once per block. Workgroup ids are
+// dealt round-robin over the 8 XCDs; the requests go to the XCDs in runs, so that
+// neighbouring requests - which tend to share a prefix, i.e. keys - meet in one L2 and run at the
+// same time, while any long stretch of the batch (say, its longest requests, if the caller sorted
+// it) is still spread over all XCDs.
+// The run is 2^lg_run requests: 64 in a large batch, shorter in a small one so that every XCD
+// still gets its share (64 requests: runs of 1, i.e. plain round-robin).
+__device__ __forceinline__ int request_of_workgroup(unsigned id, int lg_run) {
+  const unsigned xcd = id & 7u, k = id >> 3;  // k-th workgroup of this XCD
+  return (int)((((k >> lg_run) * 8u + xcd) << lg_run) + (k & ((1u << lg_run) - 1u)));
+}
+inline int request_run_lg(int n_req) {
+  int lg = 0;
+  while (lg < 6 && (n_req >> (lg + 7)) > 0) ++lg;  // at least 8 runs per XCD before runs grow
+  return lg;
+}
+inline unsigned workgroups_for_requests(int n_req, int lg_run) {
+  const unsigned per_round = 8u << lg_run;
+  return ((unsigned)n_req + per_round - 1) / per_round * per_round;
+}
+
 inline Table table_of(const aibx_index* ix) {
   Table t;
   t.slots = ix->slots;
