@@ -113,8 +113,8 @@ int aibx_block_hash(const int32_t* d_tokens, const int64_t* d_tok_off, const int
  */
 typedef struct aibx_index aibx_index_t; /* opaque host handle */
 
-/* Bytes of device storage a table of n_slots needs (20 per slot: the 16-byte slot and a 4-byte
- * usage word). n_slots: power of two, 8 <= n_slots <= 2^36.
+/* Bytes of device storage a table of n_slots needs (21 per slot: the 16-byte slot, a 4-byte
+ * usage word and a tag byte). n_slots: power of two, 8 <= n_slots <= 2^36.
  * Errors: INVALID_ARG (null out), UNSUPPORTED. */
 int aibx_index_storage_bytes(uint64_t n_slots, size_t* out_bytes);
 

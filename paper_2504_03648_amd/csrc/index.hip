@@ -3,7 +3,8 @@
 // prefix-cache-aware policy, Section 3.2.2). Semantics are stated in aibx.h.
 //
 // Behind the slots the storage holds one 32-bit usage word per slot (touch count and last epoch)
-// for the victim selection of the eviction policy.
+// for the victim selection of the eviction policy, and behind those one tag byte per slot, which
+// is all a lookup reads until a tag matches (index_device.h).
 // Table: open addressing over buckets of 8 slots; a bucket is one 128-byte line holding its 8 keys
 // and then its 8 values. Key 0 = EMPTY, key 2^64-1 = TOMBSTONE. A key lives in the first bucket of
 // its probe sequence (home, home+step, home+2*step, ... mod n_buckets, step odd and key-dependent)
@@ -192,6 +193,7 @@ __global__ __launch_bounds__(kIndexThreads) void index_insert_kernel(Table t, So
       if (old == cand_expected) {  // the slot is ours
         store_value(cslot + kBucket, val);
         t.usage[cand_bucket * kBucket + cand_slot] = use;
+        t.tags[cand_bucket * kBucket + cand_slot] = (unsigned char)tag_of(key);
         ++n_ins;
         break;
       }
@@ -254,7 +256,10 @@ __global__ __launch_bounds__(kIndexThreads) void index_evict_kernel(
       u64* slot = bucket + hit;
       const u64 old = atomicCAS((unsigned long long*)slot, (unsigned long long)key,
                                 (unsigned long long)(any_empty ? kEmpty : kTomb));
-      if (old == key) result = slot[kBucket];  // otherwise another entry of this batch removed it first
+      if (old == key) {  // otherwise another entry of this batch removed it first
+        result = slot[kBucket];
+        t.tags[b * kBucket + hit] = (unsigned char)(any_empty ? kTagEmpty : kTagTomb);
+      }
       break;
     }
     if (any_empty || probes + 1 >= t.probe_limit) break;
@@ -321,9 +326,9 @@ __global__ __launch_bounds__(kIndexThreads) void index_age_kernel(u32* usage, u6
 }
 
 // ---- whole-table passes ------------------------------------------------------------------------
-__global__ __launch_bounds__(kIndexThreads) void fill_zero_kernel(uint4* p, u64 n_vec) {
-  for (u64 i = (u64)blockIdx.x * kIndexThreads + threadIdx.x; i < n_vec; i += (u64)gridDim.x * kIndexThreads)
-    p[i] = uint4{0, 0, 0, 0};
+__global__ __launch_bounds__(kIndexThreads) void fill_zero_kernel(u64* p, u64 n_words) {
+  for (u64 i = (u64)blockIdx.x * kIndexThreads + threadIdx.x; i < n_words; i += (u64)gridDim.x * kIndexThreads)
+    p[i] = 0ull;
 }
 
 __global__ void zero_word_kernel(u64* p, int n) {
@@ -430,15 +435,14 @@ int aibx_index_storage_bytes(uint64_t n_slots, size_t* out_bytes) {
   if (!out_bytes) return AIBX_ERR_INVALID_ARG;
   const int rc = check_slots(n_slots);
   if (rc != AIBX_OK) return rc;
-  *out_bytes = (size_t)n_slots * (kSlotBytes + kUsageBytes);
+  *out_bytes = (size_t)n_slots * kStorageBytesPerSlot;
   return AIBX_OK;
 }
 
 int aibx_index_clear(aibx_index_t* index, void* stream) {
   if (!index) return AIBX_ERR_INVALID_ARG;
-  const u64 n_vec = index->n_slots * (kSlotBytes + kUsageBytes) / 16;  // slots and usage words
-  fill_zero_kernel<<<pass_grid(n_vec), kIndexThreads, 0, as_stream(stream)>>>(
-      reinterpret_cast<uint4*>(index->slots), n_vec);
+  const u64 n_words = index->n_slots * kStorageBytesPerSlot / 8;  // slots, usage words and tags (n_slots % 8 == 0)
+  fill_zero_kernel<<<pass_grid(n_words), kIndexThreads, 0, as_stream(stream)>>>(index->slots, n_words);
   return launch_status();
 }
 
@@ -448,11 +452,12 @@ int aibx_index_create(void* d_storage, size_t bytes, uint64_t n_slots, void* str
   *out = nullptr;
   const int rc = check_slots(n_slots);
   if (rc != AIBX_OK) return rc;
-  if (bytes < (size_t)n_slots * (kSlotBytes + kUsageBytes)) return AIBX_ERR_INVALID_ARG;
+  if (bytes < (size_t)n_slots * kStorageBytesPerSlot) return AIBX_ERR_INVALID_ARG;
   if (!aligned(d_storage, 256)) return AIBX_ERR_ALIGN;
   aibx_index* ix = new aibx_index();
   ix->slots = static_cast<u64*>(d_storage);
   ix->usage = reinterpret_cast<u32*>(ix->slots + 2 * n_slots);
+  ix->tags = reinterpret_cast<unsigned char*>(ix->usage + n_slots);
   ix->n_slots = n_slots;
   ix->n_buckets = n_slots / kBucket;
   ix->lg_buckets = 0;

@@ -8,6 +8,7 @@
 struct aibx_index {
   aibx::u64* slots;       // device, 2*n_slots words: buckets of 8 keys followed by their 8 values
   aibx::u32* usage;       // device, n_slots words behind the slots: (touch count << 24) | last epoch
+  unsigned char* tags;    // device, n_slots bytes behind the usage words: one tag per slot
   aibx::u64 n_slots;
   aibx::u64 n_buckets;    // n_slots / 8, power of two
   int lg_buckets;
@@ -24,7 +25,8 @@ constexpr u64 kHomeMul = 0x9E3779B97F4A7C15ull;  // multiplicative (Fibonacci) b
 constexpr int kIndexThreads = 256;
 constexpr int kWavesPerGroup = kIndexThreads / kWave;
 
-constexpr int kSlotBytes = 16, kUsageBytes = 4;  // storage per slot: the slot, then its usage word
+constexpr int kSlotBytes = 16, kUsageBytes = 4, kTagBytes = 1;  // storage per slot: slot, usage word, tag
+constexpr int kStorageBytesPerSlot = kSlotBytes + kUsageBytes + kTagBytes;
 constexpr u32 kEpochMask = 0xFFFFFFu;             // usage word: [31:24] touch count, [23:0] last epoch
 
 // A key is stored within the first kMaxProbeBuckets buckets of its probe sequence or not at all, and
@@ -37,6 +39,7 @@ constexpr u64 kMaxProbeBuckets = 4096;
 struct Table {
   u64* slots;
   u32* usage;
+  unsigned char* tags;
   u64 bucket_mask;
   u64 probe_limit;  // min(n_buckets, kMaxProbeBuckets): buckets of a probe sequence that are ever used
   int shift;  // 64 - lg(n_buckets); home = (key * kHomeMul) >> shift (0 buckets bits -> 0)
@@ -74,9 +77,31 @@ __device__ __forceinline__ void load_bucket_keys(const u64* bucket, u64 (&keys)[
   }
 }
 
+// ---- tags --------------------------------------------------------------------------------------
+// One byte per slot, the 8 tags of a bucket in one 64-bit word: 0 = the slot is EMPTY, 0xFF = it
+// is a TOMBSTONE, anything else = 8 bits of the key's product that neither the home bucket nor the
+// probe step use. The update kernels write a slot's tag after they have won its key word, so
+// between launches the tags mirror the keys exactly. A lookup walks the tags only - an eighth of
+// the bytes of the key words, so the tags of a table stay in cache where its slots do not (16 Mi
+// slots: 16 MiB of tags against 256 MiB of slots) - and touches a slot only where the tag matches:
+// always for a key that is present, with probability 1/254 per occupied slot for one that is not.
+constexpr unsigned kTagEmpty = 0x00u, kTagTomb = 0xFFu;
+constexpr u64 kOnes = 0x0101010101010101ull, kLow7 = 0x7F7F7F7F7F7F7F7Full;
+
+__device__ __forceinline__ unsigned tag_of(u64 key) {
+  const unsigned x = (unsigned)((key * kHomeMul) >> 24) & 0xFFu;
+  return x == kTagEmpty ? 1u : (x == kTagTomb ? 0xFEu : x);
+}
+// 0x80 in every byte of x that is zero, 0 elsewhere (exact: no carry crosses a byte)
+__device__ __forceinline__ u64 zero_bytes(u64 x) { return ~(((x & kLow7) + kLow7) | x | kLow7); }
+
+__device__ __forceinline__ const u64* tag_word(const Table& t, u64 b) {
+  return reinterpret_cast<const u64*>(t.tags) + b;
+}
+
 // ---- lookup ------------------------------------------------------------------------------------
-// One lane per key: the lane reads the keys of its key's bucket (64 bytes) and compares them
-// itself. Random line reads on this GPU are bound by the number of lines requested (about 55-80 G
+// One lane per key: the lane reads the 8 tags of its key's bucket (one 8-byte load) and compares
+// them itself; random reads on this GPU are bound by the number of lines requested (about 55-80 G
 // lines/s whether a line is fetched by one lane or by eight), so this costs the memory system no
 // more than a cooperative read and needs no cross-lane work at all.
 // Read-only: plain cached loads. Returns the key's value or kNoValue.
@@ -85,20 +110,21 @@ __device__ __forceinline__ u64 lookup_one(const Table& t, u64 key, bool valid) {
   bool open = valid && key != kEmpty && key != kTomb;
   u64 b = home_bucket(t, key);
   const u64 step = probe_step(key);
+  const u64 mine = (u64)tag_of(key) * kOnes;
   for (u64 seen_buckets = 0; open; ++seen_buckets) {
-    const u64* bucket = bucket_words(t, b);
-    u64 k[kBucket];
-    load_bucket_keys(bucket, k);
+    const u64 tags = *tag_word(t, b);
     bool ends = seen_buckets + 1 >= t.probe_limit;  // that was the last bucket a key may be in
-    int hit = -1;
-#pragma unroll
-    for (int j = 0; j < kBucket; ++j) {
-      if (k[j] == key) hit = j;
-      ends |= k[j] == kEmpty;  // a bucket with an EMPTY slot ends the probe sequence
-    }
-    if (hit >= 0) {
-      result = bucket[kBucket + hit];
-      ends = true;
+    ends |= zero_bytes(tags) != 0;                  // a bucket with an EMPTY slot ends the probe sequence
+    u64 cand = zero_bytes(tags ^ mine);             // slots whose tag equals the key's
+    const u64* bucket = bucket_words(t, b);
+    while (cand) {
+      const int j = (__ffsll((unsigned long long)cand) - 1) >> 3;
+      cand &= cand - 1;
+      if (bucket[j] == key) {
+        result = bucket[kBucket + j];
+        ends = true;
+        cand = 0;
+      }
     }
     open = !ends;
     b = (b + step) & t.bucket_mask;
@@ -131,6 +157,7 @@ inline Table table_of(const aibx_index* ix) {
   Table t;
   t.slots = ix->slots;
   t.usage = ix->usage;
+  t.tags = ix->tags;
   t.bucket_mask = ix->n_buckets - 1;
   t.probe_limit = ix->n_buckets < kMaxProbeBuckets ? ix->n_buckets : kMaxProbeBuckets;
   t.shift = 64 - ix->lg_buckets;

@@ -39,8 +39,8 @@ def test_version_and_strerror(lib):
 
 def test_storage_bytes_rules(lib):
     out = C.c_size_t()
-    assert lib.aibx_index_storage_bytes(1 << 20, C.byref(out)) == 0 and out.value == 20 << 20
-    assert lib.aibx_index_storage_bytes(8, C.byref(out)) == 0 and out.value == 160
+    assert lib.aibx_index_storage_bytes(1 << 20, C.byref(out)) == 0 and out.value == 21 << 20
+    assert lib.aibx_index_storage_bytes(8, C.byref(out)) == 0 and out.value == 168
     for bad in (0, 4, 12, 1000, (1 << 20) + 8, 1 << 40):
         assert lib.aibx_index_storage_bytes(bad, C.byref(out)) == -3
     assert lib.aibx_index_storage_bytes(64, None) == -1
