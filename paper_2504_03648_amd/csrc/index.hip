@@ -285,34 +285,16 @@ __global__ __launch_bounds__(kIndexThreads) void index_evict_kernel(
 __global__ __launch_bounds__(kIndexThreads) void index_touch_kernel(Table t, const u64* __restrict__ keys,
                                                                    int64_t n, u32 epoch) {
   for (int64_t i = (int64_t)blockIdx.x * kIndexThreads + threadIdx.x; i < n; i += (int64_t)gridDim.x * kIndexThreads) {
-    const u64 key = keys[i];
-    if (key == kEmpty || key == kTomb) continue;
-    const u64 step = probe_step(key);
-    u64 b = home_bucket(t, key);
-    for (u64 seen_buckets = 0;; ++seen_buckets) {
-      u64 k[kBucket];
-      load_bucket_keys(bucket_words(t, b), k);
-      int hit = -1;
-      bool ends = seen_buckets + 1 >= t.probe_limit;
-#pragma unroll
-      for (int j = 0; j < kBucket; ++j) {
-        if (k[j] == key) hit = j;
-        ends |= k[j] == kEmpty;
-      }
-      if (hit >= 0) {
-        u32* word = t.usage + b * kBucket + hit;
-        u32 seen = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        for (;;) {  // ends: every failed swap means another touch of this key went through
-          const u32 count = seen >> 24, last = seen & kEpochMask;
-          const u32 want = ((count < 255 ? count + 1 : 255u) << 24) | (epoch > last ? epoch : last);
-          const u32 old = atomicCAS(word, seen, want);
-          if (old == seen) break;
-          seen = old;
-        }
-        break;
-      }
-      if (ends) break;
-      b = (b + step) & t.bucket_mask;
+    const int64_t slot = find_slot(t, keys[i], true);
+    if (slot < 0) continue;  // absent keys are ignored
+    u32* word = t.usage + slot;
+    u32 seen = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (;;) {  // ends: every failed swap means another touch of this key went through
+      const u32 count = seen >> 24, last = seen & kEpochMask;
+      const u32 want = ((count < 255 ? count + 1 : 255u) << 24) | (epoch > last ? epoch : last);
+      const u32 old = atomicCAS(word, seen, want);
+      if (old == seen) break;
+      seen = old;
     }
   }
 }

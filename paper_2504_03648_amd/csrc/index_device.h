@@ -104,9 +104,9 @@ __device__ __forceinline__ const u64* tag_word(const Table& t, u64 b) {
 // them itself; random reads on this GPU are bound by the number of lines requested (about 55-80 G
 // lines/s whether a line is fetched by one lane or by eight), so this costs the memory system no
 // more than a cooperative read and needs no cross-lane work at all.
-// Read-only: plain cached loads. Returns the key's value or kNoValue.
-__device__ __forceinline__ u64 lookup_one(const Table& t, u64 key, bool valid) {
-  u64 result = kNoValue;
+// Read-only: plain cached loads. find_slot returns the key's slot (8*bucket + j) or -1.
+__device__ __forceinline__ int64_t find_slot(const Table& t, u64 key, bool valid) {
+  int64_t found = -1;
   bool open = valid && key != kEmpty && key != kTomb;
   u64 b = home_bucket(t, key);
   const u64 step = probe_step(key);
@@ -121,7 +121,7 @@ __device__ __forceinline__ u64 lookup_one(const Table& t, u64 key, bool valid) {
       const int j = (__ffsll((unsigned long long)cand) - 1) >> 3;
       cand &= cand - 1;
       if (bucket[j] == key) {
-        result = bucket[kBucket + j];
+        found = (int64_t)(b * kBucket + j);
         ends = true;
         cand = 0;
       }
@@ -129,7 +129,13 @@ __device__ __forceinline__ u64 lookup_one(const Table& t, u64 key, bool valid) {
     open = !ends;
     b = (b + step) & t.bucket_mask;
   }
-  return result;
+  return found;
+}
+
+// The key's value or kNoValue.
+__device__ __forceinline__ u64 lookup_one(const Table& t, u64 key, bool valid) {
+  const int64_t s = find_slot(t, key, valid);
+  return s < 0 ? kNoValue : t.slots[key_word_of_slot((u64)s) + kBucket];
 }
 
 // Request -> workgroup map of the kernels that probe the index once per block. Workgroup ids are
