@@ -35,6 +35,17 @@ __host__ __device__ constexpr u64 ipow(u64 base, u64 e) {
   return r;
 }
 
+// K2^(i+1) for i < 64: the weight of the chain state entering a lane's row (or tile) at the lane's
+// block. Read from constant memory: forming the power with multiplies cost every wavefront about
+// a fifth of a tile's arithmetic before its first token.
+struct ChainPowers {
+  u64 v[kWave];
+  constexpr ChainPowers() : v() {
+    for (int i = 0; i < kWave; ++i) v[i] = ipow(0xBB67AE8584CAA73Bull, (u64)i + 1);
+  }
+};
+__constant__ const ChainPowers kChainPowers{};
+
 __device__ __forceinline__ u64 fin(u64 x) {
   x ^= x >> 32;
   x *= K1;
@@ -140,14 +151,7 @@ __global__ __launch_bounds__(kHashWaves* kWave) void block_hash_pow2_kernel(
   // K2^(pos+1), pos = lane within its row of 16: weight of the state entering the row
   constexpr int kRows = kNB >= 16 ? kNB / 16 : 1;
   const int row = lane >> 4;
-  u64 row_w = 1;
-  {
-    u64 sq = K2;
-    for (int bit = 0; bit < 5; ++bit) {
-      if (((lane & 15) + 1) >> bit & 1) row_w *= sq;
-      sq *= sq;
-    }
-  }
+  const u64 row_w = kChainPowers.v[lane & 15];
   // lane that holds block `lane`'s sum after the butterfly
   const int src_lane = ((lane % kGroups) * kB + ((lane / kGroups) << (kLgB - 4))) & (kWave - 1);
 
@@ -352,14 +356,7 @@ __global__ __launch_bounds__(kGeneralWaves* kWave) void block_hash_general_kerne
   }
   __syncthreads();  // digests written by this workgroup are visible to it after the barrier
   if (wave != 0) return;
-  u64 carry_w = 1;
-  {
-    u64 sq = K2;
-    for (int bit = 0; bit < 7; ++bit) {
-      if ((lane + 1) >> bit & 1) carry_w *= sq;
-      sq *= sq;
-    }
-  }
+  const u64 carry_w = kChainPowers.v[lane];
   u64 carry = fin(seed ^ K3);
   for (int64_t base = 0; base < n_r; base += kWave) {
     const int64_t j = base + lane;
