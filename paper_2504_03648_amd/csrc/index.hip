@@ -26,10 +26,11 @@ namespace {
 // Measured alternatives that lost: one wavefront per request (-20 %: long requests serialise),
 // a flat pass over all blocks plus a first-miss pass (-15 %: second launch, values re-read), and
 // lanes that refill themselves with their next key (no gain: the bound is lines requested).
-__global__ __launch_bounds__(kIndexThreads) void prefix_match_kernel(
+template <int kWaves>
+__global__ __launch_bounds__(kWaves* kWave) void prefix_match_kernel(
     Table t, const u64* __restrict__ hashes, const int64_t* __restrict__ blk_off,
     u64* __restrict__ values_out, int32_t* __restrict__ match_len, int n_req, int lg_run) {
-  __shared__ int lds_first[kWavesPerGroup];
+  __shared__ int lds_first[kWaves];
   // (config 2, groups of 8 neighbouring requests sharing half their blocks: 58 -> 77 G probes/s
   // against request = workgroup id)
   const int r = request_of_workgroup(blockIdx.x, lg_run);
@@ -37,23 +38,31 @@ __global__ __launch_bounds__(kIndexThreads) void prefix_match_kernel(
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int64_t b0 = blk_off[r];
   const int64_t n_r = blk_off[r + 1] - b0;
+  // a request of at most 64 blocks is one wavefront's work: the others leave, and no barrier is needed
+  const bool solo = kWaves == 1 || n_r <= kWave;
+  if (solo && wave != 0) return;
+  constexpr int kStride = kWaves * kWave;
   int64_t first_miss = n_r;
   int64_t base = (int64_t)wave * kWave;
   u64 k_next = base + lane < n_r ? hashes[b0 + base + lane] : kEmpty;
-  for (; base < n_r; base += kIndexThreads) {
+  for (; base < n_r; base += kStride) {
     const bool valid = base + lane < n_r;
     const u64 k = k_next;
-    k_next = base + kIndexThreads + lane < n_r ? hashes[b0 + base + kIndexThreads + lane] : kEmpty;
+    k_next = base + kStride + lane < n_r ? hashes[b0 + base + kStride + lane] : kEmpty;
     const u64 v = lookup_one(t, k, valid);
     if (valid && values_out) values_out[b0 + base + lane] = v;
     const u64 miss = __ballot(valid && v == kNoValue);
     if (miss && first_miss == n_r) first_miss = base + (__ffsll((unsigned long long)miss) - 1);
   }
+  if (solo) {
+    if (lane == 0) match_len[r] = (int)first_miss;
+    return;
+  }
   if (lane == 0) lds_first[wave] = (int)first_miss;
   __syncthreads();
   if (threadIdx.x == 0) {
     int m = lds_first[0];
-    for (int w = 1; w < kWavesPerGroup; ++w) m = lds_first[w] < m ? lds_first[w] : m;
+    for (int w = 1; w < kWaves; ++w) m = lds_first[w] < m ? lds_first[w] : m;
     match_len[r] = m;
   }
 }
@@ -560,8 +569,15 @@ int aibx_prefix_match(const aibx_index_t* index, const uint64_t* d_hashes, const
   if (!aligned(d_hashes, 8) || !aligned(d_blk_off, 8) || !aligned(d_values_out, 8) || !aligned(d_match_len, 4))
     return AIBX_ERR_ALIGN;
   const int lg_run = request_run_lg(n_req);
-  prefix_match_kernel<<<workgroups_for_requests(n_req, lg_run), kIndexThreads, 0, as_stream(stream)>>>(
-      table_of(index), d_hashes, d_blk_off, d_values_out, d_match_len, n_req, lg_run);
+  const unsigned grid = workgroups_for_requests(n_req, lg_run);
+  // Thousands of requests averaging at most 64 blocks: one wavefront per request and nothing else.
+  // Otherwise four per request (those of a short request beyond the first leave at once).
+  if (n_req >= 4096 && n_blocks_total <= (int64_t)n_req * kWave)
+    prefix_match_kernel<1><<<grid, kWave, 0, as_stream(stream)>>>(table_of(index), d_hashes, d_blk_off,
+                                                                   d_values_out, d_match_len, n_req, lg_run);
+  else
+    prefix_match_kernel<kWavesPerGroup><<<grid, kIndexThreads, 0, as_stream(stream)>>>(
+        table_of(index), d_hashes, d_blk_off, d_values_out, d_match_len, n_req, lg_run);
   return launch_status();
 }
 

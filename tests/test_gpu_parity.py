@@ -77,16 +77,19 @@ def test_block_hash_many_requests(hip, B):
     assert np.array_equal(got, want)
 
 
-def test_match_many_requests():
-    """Thousands of short ragged requests in one call."""
-    rng = np.random.default_rng(5)
+@pytest.mark.parametrize("top", [200, 90])
+def test_match_many_requests(top):
+    """Thousands of short ragged requests in one call: four wavefronts per request (mean above 64
+    blocks; requests of up to 64 blocks are left to the first of them) or one per request (mean
+    below), each with a long request among them."""
+    rng = np.random.default_rng(5 + top)
     keys = np.unique(rng.integers(1, 2**63, size=60000, dtype=np.uint64))
     gi, oi = HipIndex(1 << 16), oracle.Index(1 << 16)
     present = keys[: len(keys) // 2]
     for ix in (gi, oi):
         ix.insert(present, present >> np.uint64(7))
-    sizes = rng.integers(0, 200, size=5000)
-    sizes[17] = 1000
+    sizes = rng.integers(0, top, size=5000)
+    sizes[17], sizes[18], sizes[4999] = 1000, 64, 65
     blk_off = np.zeros(len(sizes) + 1, dtype=np.int64)
     np.cumsum(sizes, out=blk_off[1:])
     h = rng.choice(keys, size=int(blk_off[-1]))
