@@ -134,7 +134,9 @@ struct MatchOut {
 };
 
 template <int kB, int kHashWaves, bool kMatch>
-__global__ __launch_bounds__(kHashWaves* kWave) void block_hash_pow2_kernel(
+// (7 wavefronts per SIMD: the register budget this sets - 72 instead of 95 with the lookups - costs
+// no spills and is worth 2-7 % on the fused kernel)
+__global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_eu(7, 7))) void block_hash_pow2_kernel(
     const int32_t* __restrict__ tokens, const int64_t* __restrict__ tok_off,
     const int64_t* __restrict__ blk_off, int n_req, int lg_run, u64 seed, u64* __restrict__ hash_out,
     MatchOut mo, int solo_tiles) {
@@ -374,7 +376,8 @@ __global__ __launch_bounds__(kGeneralWaves* kWave) void block_hash_general_kerne
 namespace aibx {
 namespace {
 
-constexpr int kSoloTiles = 8;  // tiles of 1024 tokens
+constexpr int kSoloTiles = 8;       // tiles of 1024 tokens; hashing alone
+constexpr int kSoloTilesFused = 4;  // with the lookups in the launch a wavefront's tile takes longer, so long requests are shared earlier
 
 template <bool kMatch>
 int launch_hash(const int32_t* d_tokens, const int64_t* d_tok_off, const int64_t* d_blk_off, int32_t n_req,
@@ -384,14 +387,15 @@ int launch_hash(const int32_t* d_tokens, const int64_t* d_tok_off, const int64_t
   //    shared by the four, so that a small batch finishes in few serial tiles;
   //  - thousands of requests averaging under two tiles: one wavefront per request and nothing else
   //    (workgroups of four with three idle wavefronts cost +50 % on 100,000 one-tile requests);
-  //  - thousands of longer requests: the GPU is full anyway, so a request of up to 8 tiles is hashed
+  //  - thousands of longer requests: the GPU is full anyway, so a request of up to 8 tiles (4 with the
+  //    lookups in the launch) is hashed
   //    by one wavefront of its workgroup, and only longer ones - which would otherwise run on as
   //    the batch's tail - by the four together. Measured on 4 Mi-block batches against one
   //    wavefront for every request: lognormal lengths -15 % time (-24 % with the lookups in the same
   //    launch), uniform 4-tile requests equal, uniform 16-tile requests of 64-token blocks -7 % (+5 %).
   const int64_t mean_tokens = n_blocks_total * (int64_t)block_size / n_req;
   const bool single = n_req >= 4096 && mean_tokens < 2 * kTileTokens;
-  const int solo_tiles = n_req < 4096 ? 1 : kSoloTiles;
+  const int solo_tiles = n_req < 4096 ? 1 : (kMatch ? kSoloTilesFused : kSoloTiles);
   const int lg_run = request_run_lg(n_req);
   dim3 grid(kMatch ? workgroups_for_requests(n_req, lg_run) : (unsigned)n_req);
 #define AIBX_LAUNCH_HASH(B)                                                                                 \
