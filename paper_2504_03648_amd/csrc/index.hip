@@ -294,7 +294,8 @@ __global__ __launch_bounds__(kIndexThreads) void index_evict_kernel(
 __global__ __launch_bounds__(kIndexThreads) void index_touch_kernel(Table t, const u64* __restrict__ keys,
                                                                    int64_t n, u32 epoch) {
   for (int64_t i = (int64_t)blockIdx.x * kIndexThreads + threadIdx.x; i < n; i += (int64_t)gridDim.x * kIndexThreads) {
-    const int64_t slot = find_slot(t, keys[i], true);
+    u64 unused_value;
+    const int64_t slot = find_slot(t, keys[i], true, unused_value);
     if (slot < 0) continue;  // absent keys are ignored
     u32* word = t.usage + slot;
     u32 seen = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

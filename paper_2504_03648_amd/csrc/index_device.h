@@ -104,8 +104,10 @@ __device__ __forceinline__ const u64* tag_word(const Table& t, u64 b) {
 // them itself; random reads on this GPU are bound by the number of lines requested (about 55-80 G
 // lines/s whether a line is fetched by one lane or by eight), so this costs the memory system no
 // more than a cooperative read and needs no cross-lane work at all.
-// Read-only: plain cached loads. find_slot returns the key's slot (8*bucket + j) or -1.
-__device__ __forceinline__ int64_t find_slot(const Table& t, u64 key, bool valid) {
+// Read-only: plain cached loads. find_slot returns the key's slot (8*bucket + j) or -1, and the
+// slot's value through value_out: key and value of a candidate slot sit in one 128-byte line and
+// are requested together, so a probe that hits makes two dependent accesses (tags, slot), not three.
+__device__ __forceinline__ int64_t find_slot(const Table& t, u64 key, bool valid, u64& value_out) {
   int64_t found = -1;
   bool open = valid && key != kEmpty && key != kTomb;
   u64 b = home_bucket(t, key);
@@ -120,8 +122,10 @@ __device__ __forceinline__ int64_t find_slot(const Table& t, u64 key, bool valid
     while (cand) {
       const int j = (__ffsll((unsigned long long)cand) - 1) >> 3;
       cand &= cand - 1;
-      if (bucket[j] == key) {
+      const u64 slot_key = bucket[j], slot_value = bucket[kBucket + j];
+      if (slot_key == key) {
         found = (int64_t)(b * kBucket + j);
+        value_out = slot_value;
         ends = true;
         cand = 0;
       }
@@ -134,8 +138,9 @@ __device__ __forceinline__ int64_t find_slot(const Table& t, u64 key, bool valid
 
 // The key's value or kNoValue.
 __device__ __forceinline__ u64 lookup_one(const Table& t, u64 key, bool valid) {
-  const int64_t s = find_slot(t, key, valid);
-  return s < 0 ? kNoValue : t.slots[key_word_of_slot((u64)s) + kBucket];
+  u64 value = kNoValue;
+  (void)find_slot(t, key, valid, value);
+  return value;
 }
 
 // Request -> workgroup map of the kernels that probe the index once per block. Workgroup ids are
