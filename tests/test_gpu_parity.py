@@ -184,6 +184,10 @@ def test_index_random_ops_against_oracle(n_slots, seed):
     assert np.array_equal(gk, ok) and np.array_equal(gv, ov)
     assert np.array_equal(gi.counters_insert, oi.counters_insert)
     assert np.array_equal(gi.counters_evict, oi.counters_evict)
+    # every key that ever existed, looked up once more: the tags a lookup walks mirror the keys
+    gv, gm = gi.match(universe, [0, len(universe)])
+    ov, om = oi.match(universe, [0, len(universe)])
+    assert np.array_equal(gv, ov) and np.array_equal(gm, om)
 
 
 def test_index_beyond_full_is_bounded_and_consistent():
