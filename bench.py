@@ -460,10 +460,16 @@ def survey_config(torch, aibx, cfg, layout=None):
     ms_h, _ = time_calls(torch, lambda: aibx.aibx_block_hash(d_tok, d_to, d_bo, Rs, Ns, B, 0, h), 10)
     ms_m, _ = time_calls(torch, lambda: aibx.aibx_prefix_match(ix, h, d_bo, Rs, Ns, v, m), 10)
     ms_f, _ = time_calls(torch, lambda: aibx.aibx_hash_match(ix, d_tok, d_to, d_bo, Rs, Ns, B, 0, h, v, m), 10)
+    # match lengths only (what a routing decision needs): no hashes, no per-block values written, and the
+    # kernels stop working on a request behind its first miss
+    ms_len, _ = time_calls(torch, lambda: aibx.aibx_hash_match(ix, d_tok, d_to, d_bo, Rs, Ns, B, 0, None, None, m), 10)
+    ms_mlen, _ = time_calls(torch, lambda: aibx.aibx_prefix_match(ix, h, d_bo, Rs, Ns, None, m), 10)
     per = 4 * B + 8 + 8 + 64 + 8
     rate = Ns / ((ms_h + ms_m) * 1e-3)
     out["scaled"] = {"requests": Rs, "blocks": Ns, "hash_ms": ms_h, "match_ms": ms_m, "blocks_per_s": rate,
                      "roofline_frac": rate * per / 1e9 / HBM_PEAK_GBPS, "bytes_per_block": per,
+                     "lengths_only_one_launch_ms": ms_len, "lengths_only_match_ms": ms_mlen,
+                     "mean_match_fraction": float(m.float().sum().item()) / Ns,
                      "one_launch_ms": ms_f, "one_launch_roofline_frac": Ns / (ms_f * 1e-3) * per / 1e9 / HBM_PEAK_GBPS,
                      "index_slots": wl.n_slots, "load_factor": wl.load_factor}
     # routing decision on the scaled batch: values read as pod sets (low 8 bits), 8 pods

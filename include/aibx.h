@@ -206,6 +206,8 @@ int aibx_index_dump(const aibx_index_t* index, uint64_t* d_keys_out, uint64_t* d
  * its value but does not extend the match).
  *   d_hashes uint64[n_blocks_total]; d_blk_off int64[n_req+1] as for aibx_block_hash;
  *   d_values_out uint64[n_blocks_total], nullable; d_match_len int32[n_req].
+ * With d_values_out NULL only the match lengths are produced (all a routing decision needs), and
+ * the kernel stops probing a request behind its first missing block.
  * Errors: INVALID_ARG, ALIGN, HIP. */
 int aibx_prefix_match(const aibx_index_t* index, const uint64_t* d_hashes,
                       const int64_t* d_blk_off, int32_t n_req, int64_t n_blocks_total,
@@ -218,6 +220,8 @@ int aibx_prefix_match(const aibx_index_t* index, const uint64_t* d_hashes,
  *                those sizes run as the two separate launches);
  *   d_values_out uint64[n_blocks_total], nullable; d_match_len int32[n_req];
  *   every other argument as in aibx_block_hash / aibx_prefix_match.
+ * With d_values_out NULL the lookups of a request stop behind its first missing block, and with
+ * d_hash_out NULL as well so does the hashing of most requests: tokens in, match lengths out.
  * Errors: INVALID_ARG, ALIGN, UNSUPPORTED (block size outside {16,32,64} with d_hash_out NULL), HIP. */
 int aibx_hash_match(const aibx_index_t* index, const int32_t* d_tokens, const int64_t* d_tok_off,
                     const int64_t* d_blk_off, int32_t n_req, int64_t n_blocks_total,

@@ -180,6 +180,7 @@ __global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_
   u64 pend_h = 0;
   int64_t pend_jb = 0;
   bool pend_valid = false;
+  bool miss_seen = false;  // wavefront-uniform: one of this wavefront's lookups has missed
   const int64_t n_tok = n_r * kB;  // tokens that belong to full blocks
   const int32_t* tok = tokens + tok_off[r];
   u64* out = hash_out + b0;
@@ -276,11 +277,21 @@ __global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_
     for (int r = 1; r < kRows; ++r) enter = row == r ? y[r] + ipow(K2, 16 * r) * cin : enter;
     const u64 h = out_hash(row_w * enter + local);
     if (valid && (!kMatch || hash_out)) out[jb] = h;
+    // When the caller wants no per-block values, nothing behind this wavefront's first miss can
+    // change an output any more (its tiles come in rising order): the lookups stop there, and a
+    // wavefront that hashes its request alone and writes no hashes either is done with it.
+    if constexpr (kMatch) {
+      if (!mo.values_out && miss_seen) {
+        if (solo && !hash_out) break;
+        goto tile_done;
+      }
+    }
     if constexpr (kMatch && kPack == 1) {
       const u64 v = lookup_one(mo.table, h, valid);
       if (valid && mo.values_out) mo.values_out[b0 + jb] = v;
       const u64 miss = __ballot(valid && v == kNoValue);
       if (miss && first_miss == n_r) first_miss = tile * kNB + (__ffsll((unsigned long long)miss) - 1);
+      miss_seen = miss != 0 || miss_seen;
     }
     if constexpr (kMatch && kPack > 1) {
       // A tile of larger blocks fills only kNB of the 64 lanes. Its hashes are parked in lane group
@@ -297,10 +308,13 @@ __global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_
       if (slot == kPack - 1 || tile0 + stride >= n_tiles) {
         const u64 v = lookup_one(mo.table, pend_h, pend_valid);
         if (pend_valid && mo.values_out) mo.values_out[b0 + pend_jb] = v;
-        if (pend_valid && v == kNoValue && pend_jb < first_miss) first_miss = pend_jb;
+        const bool missed = pend_valid && v == kNoValue;
+        if (missed && pend_jb < first_miss) first_miss = pend_jb;
+        miss_seen = __ballot(missed) != 0 || miss_seen;
         pend_valid = false;
       }
     }
+  tile_done:
     if (!solo) {
       // chain state after all tiles of this iteration (only used if another iteration follows,
       // in which case every tile of this one was full)

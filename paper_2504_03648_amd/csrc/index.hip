@@ -53,6 +53,9 @@ __global__ __launch_bounds__(kWaves* kWave) void prefix_match_kernel(
     if (valid && values_out) values_out[b0 + base + lane] = v;
     const u64 miss = __ballot(valid && v == kNoValue);
     if (miss && first_miss == n_r) first_miss = base + (__ffsll((unsigned long long)miss) - 1);
+    // without per-block values to report, nothing behind this wavefront's first miss matters
+    // (its tiles come in rising order)
+    if (!values_out && first_miss != n_r) break;
   }
   if (solo) {
     if (lane == 0) match_len[r] = (int)first_miss;

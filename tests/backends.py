@@ -169,6 +169,10 @@ class HipIndex:
         values = self.t.empty_like(h)
         mlen = self.t.full((max(n_req, 0),), -7, dtype=self.t.int32, device="cuda")
         self.a.aibx_prefix_match(self.h, h, bo, n_req, h.numel(), values, mlen)
+        # the same call without per-block values (the kernel may then stop behind a first miss)
+        mlen2 = self.t.full((max(n_req, 0),), -7, dtype=self.t.int32, device="cuda")
+        self.a.aibx_prefix_match(self.h, h, bo, n_req, h.numel(), None, mlen2)
+        assert self.t.equal(mlen, mlen2)
         return self._host_u64(values), mlen.cpu().numpy()
 
 
