@@ -220,8 +220,9 @@ int aibx_prefix_match(const aibx_index_t* index, const uint64_t* d_hashes,
  *                those sizes run as the two separate launches);
  *   d_values_out uint64[n_blocks_total], nullable; d_match_len int32[n_req];
  *   every other argument as in aibx_block_hash / aibx_prefix_match.
- * With d_values_out NULL the lookups of a request stop behind its first missing block, and with
- * d_hash_out NULL as well so does the hashing of most requests: tokens in, match lengths out.
+ * With d_hash_out and d_values_out both NULL the match lengths are the only output (tokens in,
+ * lengths out: all a routing decision needs), and the kernel stops working on a request behind its
+ * first missing block.
  * Errors: INVALID_ARG, ALIGN, UNSUPPORTED (block size outside {16,32,64} with d_hash_out NULL), HIP. */
 int aibx_hash_match(const aibx_index_t* index, const int32_t* d_tokens, const int64_t* d_tok_off,
                     const int64_t* d_blk_off, int32_t n_req, int64_t n_blocks_total,

@@ -133,7 +133,7 @@ struct MatchOut {
   int32_t* match_len;
 };
 
-template <int kB, int kHashWaves, bool kMatch>
+template <int kB, int kHashWaves, bool kMatch, bool kLengths>
 // (7 wavefronts per SIMD: the register budget this sets - 72 instead of 95 with the lookups - costs
 // no spills and is worth 2-7 % on the fused kernel)
 __global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_eu(7, 7))) void block_hash_pow2_kernel(
@@ -146,6 +146,7 @@ __global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_
   constexpr int kLgB = kB == 16 ? 4 : (kB == 32 ? 5 : 6);
   __shared__ u64 lds_aggr[2][kHashWaves];
   __shared__ int lds_first[kHashWaves];
+  __shared__ int lds_stop[2];  // a wavefront of the workgroup missed in the round of this parity
 
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
@@ -181,6 +182,10 @@ __global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_
   int64_t pend_jb = 0;
   bool pend_valid = false;
   bool miss_seen = false;  // wavefront-uniform: one of this wavefront's lookups has missed
+  constexpr bool lengths_only = kLengths;
+  if constexpr (kLengths) {
+    if (!solo && threadIdx.x < 2) lds_stop[threadIdx.x] = 0;  // ordered before its first reader by the first round's barrier
+  }
   const int64_t n_tok = n_r * kB;  // tokens that belong to full blocks
   const int32_t* tok = tokens + tok_off[r];
   u64* out = hash_out + b0;
@@ -268,6 +273,11 @@ __global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_
     if (!solo) {
       if (lane == 0) lds_aggr[parity][wave] = aggr;
       __syncthreads();
+      // match lengths as the only output: once some wavefront has missed in the previous round,
+      // every tile from here on lies behind that miss and the whole workgroup is done
+      if constexpr (kLengths) {
+        if (lds_stop[parity ^ 1]) break;
+      }
       for (int w = 0; w < wave; ++w) cin = ipow(K2, kNB) * cin + lds_aggr[parity][w];
     }
     // state entering this lane's row = y[row] + K2^(16*row) * cin; this lane's block then adds
@@ -277,12 +287,13 @@ __global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_
     for (int r = 1; r < kRows; ++r) enter = row == r ? y[r] + ipow(K2, 16 * r) * cin : enter;
     const u64 h = out_hash(row_w * enter + local);
     if (valid && (!kMatch || hash_out)) out[jb] = h;
-    // When the caller wants no per-block values, nothing behind this wavefront's first miss can
-    // change an output any more (its tiles come in rising order): the lookups stop there, and a
-    // wavefront that hashes its request alone and writes no hashes either is done with it.
-    if constexpr (kMatch) {
-      if (!mo.values_out && miss_seen) {
-        if (solo && !hash_out) break;
+    // kLengths: the caller wants neither hashes nor per-block values, so nothing behind this
+    // wavefront's first miss can change an output any more (its tiles come in rising order): a
+    // wavefront that hashes its request alone is done with it, one that shares it stops looking up
+    // and tells the others (see lds_stop).
+    if constexpr (kLengths) {
+      if (miss_seen) {
+        if (solo) break;
         goto tile_done;
       }
     }
@@ -291,7 +302,7 @@ __global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_
       if (valid && mo.values_out) mo.values_out[b0 + jb] = v;
       const u64 miss = __ballot(valid && v == kNoValue);
       if (miss && first_miss == n_r) first_miss = tile * kNB + (__ffsll((unsigned long long)miss) - 1);
-      miss_seen = miss != 0 || miss_seen;
+      if constexpr (kLengths) miss_seen = miss != 0 || miss_seen;
     }
     if constexpr (kMatch && kPack > 1) {
       // A tile of larger blocks fills only kNB of the 64 lanes. Its hashes are parked in lane group
@@ -305,16 +316,20 @@ __global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_
         pend_jb = moved_jb;
         pend_valid = tile < n_tiles && moved_jb < n_r;
       }
-      if (slot == kPack - 1 || tile0 + stride >= n_tiles) {
+      // (with match lengths as the only output a miss should be known as early as possible: no waiting)
+      if (slot == kPack - 1 || tile0 + stride >= n_tiles || lengths_only) {
         const u64 v = lookup_one(mo.table, pend_h, pend_valid);
         if (pend_valid && mo.values_out) mo.values_out[b0 + pend_jb] = v;
         const bool missed = pend_valid && v == kNoValue;
         if (missed && pend_jb < first_miss) first_miss = pend_jb;
-        miss_seen = __ballot(missed) != 0 || miss_seen;
+        if constexpr (kLengths) miss_seen = __ballot(missed) != 0 || miss_seen;
         pend_valid = false;
       }
     }
   tile_done:
+    if constexpr (kLengths) {
+      if (!solo && miss_seen && lane == 0) lds_stop[parity] = 1;
+    }
     if (!solo) {
       // chain state after all tiles of this iteration (only used if another iteration follows,
       // in which case every tile of this one was full)
@@ -393,7 +408,7 @@ namespace {
 constexpr int kSoloTiles = 8;       // tiles of 1024 tokens; hashing alone
 constexpr int kSoloTilesFused = 4;  // with the lookups in the launch a wavefront's tile takes longer, so long requests are shared earlier
 
-template <bool kMatch>
+template <bool kMatch, bool kLengths>
 int launch_hash(const int32_t* d_tokens, const int64_t* d_tok_off, const int64_t* d_blk_off, int32_t n_req,
                 int64_t n_blocks_total, int32_t block_size, u64 seed, u64* d_hash_out, MatchOut mo, hipStream_t st) {
   // Launch shape, from what the host knows (batch size and mean request length):
@@ -414,10 +429,10 @@ int launch_hash(const int32_t* d_tokens, const int64_t* d_tok_off, const int64_t
   dim3 grid(kMatch ? workgroups_for_requests(n_req, lg_run) : (unsigned)n_req);
 #define AIBX_LAUNCH_HASH(B)                                                                                 \
   if (single)                                                                                               \
-    block_hash_pow2_kernel<B, 1, kMatch><<<grid, kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off, n_req,     \
+    block_hash_pow2_kernel<B, 1, kMatch, kLengths><<<grid, kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off, n_req,     \
                                                                  lg_run, seed, d_hash_out, mo, 0);          \
   else                                                                                                      \
-    block_hash_pow2_kernel<B, 4, kMatch><<<grid, 4 * kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off, n_req, \
+    block_hash_pow2_kernel<B, 4, kMatch, kLengths><<<grid, 4 * kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off, n_req, \
                                                                      lg_run, seed, d_hash_out, mo, solo_tiles)
   switch (block_size) {
     case 16: AIBX_LAUNCH_HASH(16); break;
@@ -444,7 +459,7 @@ extern "C" int aibx_block_hash(const int32_t* d_tokens, const int64_t* d_tok_off
     return AIBX_ERR_ALIGN;
   hipStream_t st = as_stream(stream);
   if (block_size == 16 || block_size == 32 || block_size == 64)
-    return launch_hash<false>(d_tokens, d_tok_off, d_blk_off, n_req, n_blocks_total, block_size, seed, d_hash_out, MatchOut{}, st);
+    return launch_hash<false, false>(d_tokens, d_tok_off, d_blk_off, n_req, n_blocks_total, block_size, seed, d_hash_out, MatchOut{}, st);
   block_hash_general_kernel<<<dim3((u32)n_req), kGeneralWaves * kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off,
                                                                                block_size, seed, d_hash_out);
   return launch_status();
@@ -475,6 +490,9 @@ extern "C" int aibx_hash_match(const aibx_index_t* index, const int32_t* d_token
   mo.table = table_of(index);
   mo.values_out = d_values_out;
   mo.match_len = d_match_len;
-  return launch_hash<true>(d_tokens, d_tok_off, d_blk_off, n_req, n_blocks_total, block_size, seed, d_hash_out, mo,
-                           as_stream(stream));
+  if (!d_hash_out && !d_values_out)  // match lengths only
+    return launch_hash<true, true>(d_tokens, d_tok_off, d_blk_off, n_req, n_blocks_total, block_size, seed, d_hash_out,
+                                   mo, as_stream(stream));
+  return launch_hash<true, false>(d_tokens, d_tok_off, d_blk_off, n_req, n_blocks_total, block_size, seed, d_hash_out,
+                                  mo, as_stream(stream));
 }

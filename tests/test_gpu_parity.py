@@ -446,8 +446,8 @@ def test_hash_match_equals_hash_then_match(B, n_req):
     tok, tok_off, lens = _ragged(rng, n_req, 0, 30 * B if n_req > 1000 else 150 * B)
     lens[1] = 0
     lens[2] = B - 1
-    if n_req > 1000:                              # requests long enough to be shared by four wavefronts
-        lens[6], lens[7], lens[8] = 8192 + 3 * B, 8192 + 3 * B + 40, 21 * 1024 + 7
+    # requests long enough to take several rounds of four wavefronts, in large and small batches
+    lens[6], lens[7], lens[8] = 8192 + 3 * B, 8192 + 3 * B + 40, 21 * 1024 + 7
     np.cumsum(lens, out=tok_off[1:])
     tok = rng.integers(0, 32000, size=int(tok_off[-1]), dtype=np.int32)
     # requests come in pairs that share a prefix of the first of the two
