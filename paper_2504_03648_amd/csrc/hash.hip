@@ -422,6 +422,10 @@ int launch_hash(const int32_t* d_tokens, const int64_t* d_tok_off, const int64_t
   //    the batch's tail - by the four together. Measured on 4 Mi-block batches against one
   //    wavefront for every request: lognormal lengths -15 % time (-24 % with the lookups in the same
   //    launch), uniform 4-tile requests equal, uniform 16-tile requests of 64-token blocks -7 % (+5 %).
+  // Wavefronts that share a long request: four; two when only the match lengths are wanted, where
+  // everything a wavefront does behind the first miss is wasted and a round of two wastes less
+  // (tokens -> lengths on 4 Mi-block batches: -12 % to -45 % against rounds of four).
+  constexpr int kShared = kLengths ? 2 : 4;
   const int64_t mean_tokens = n_blocks_total * (int64_t)block_size / n_req;
   const bool single = n_req >= 4096 && mean_tokens < 2 * kTileTokens;
   const int solo_tiles = n_req < 4096 ? 1 : (kMatch ? kSoloTilesFused : kSoloTiles);
@@ -432,8 +436,8 @@ int launch_hash(const int32_t* d_tokens, const int64_t* d_tok_off, const int64_t
     block_hash_pow2_kernel<B, 1, kMatch, kLengths><<<grid, kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off, n_req,     \
                                                                  lg_run, seed, d_hash_out, mo, 0);          \
   else                                                                                                      \
-    block_hash_pow2_kernel<B, 4, kMatch, kLengths><<<grid, 4 * kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off, n_req, \
-                                                                     lg_run, seed, d_hash_out, mo, solo_tiles)
+    block_hash_pow2_kernel<B, kShared, kMatch, kLengths><<<grid, kShared * kWave, 0, st>>>(                          \
+        d_tokens, d_tok_off, d_blk_off, n_req, lg_run, seed, d_hash_out, mo, solo_tiles)
   switch (block_size) {
     case 16: AIBX_LAUNCH_HASH(16); break;
     case 32: AIBX_LAUNCH_HASH(32); break;
