@@ -34,8 +34,8 @@ NO_VALUE = np.uint64(0xFFFFFFFFFFFFFFFF)
 
 # HBM bytes per gather launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the same
 # counters on a plain copy of known size; valid only for the kernel source it was taken on.
-MEASURED_TRAFFIC = {"kvcopy_sha1": "096328e16844ccbf510eb5efa6d79c5528e6755f",
-                    "bytes_per_launch": 19327169539}
+MEASURED_TRAFFIC = {"kvcopy_sha1": "20f0afe104144a6cf0209e213c9b28adfa0c9a1e",
+                    "bytes_per_launch": 19327179779}
 
 
 def _u64(t):

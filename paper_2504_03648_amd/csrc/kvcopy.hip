@@ -7,7 +7,9 @@
 //    workgroups at full occupancy stream faster here than fewer workgroups that loop or that keep
 //    several vectors per lane in flight.
 //  - Loads carry the non-temporal hint; stores to the contiguous staging buffer are written
-//    through at system scope, stores into the paged pool carry the non-temporal hint.
+//    through at system scope, stores into the paged pool are written through with the
+//    non-temporal hint as well (+0.7-2 % over the hint alone on every geometry; for the staging
+//    stores the flavours are within 0.5 % of each other).
 //  - Tile -> workgroup mapping. Workgroup ids are dealt round-robin over the 8 XCDs, so with the
 //    "XCD-contiguous" map used here XCD x streams the x-th eighth of the tile sequence: each XCD
 //    (own L2, own translation cache) works on one contiguous stretch of staging and sees whole
@@ -44,7 +46,7 @@ __device__ __forceinline__ vec16 load_stream(const void* p) {
 }
 __device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(0)"); }
 __device__ __forceinline__ void store_stream(void* p, vec16 v) {
-  asm volatile("global_store_dwordx4 %0, %1, off nt" ::"v"(p), "v"(v));
+  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt" ::"v"(p), "v"(v));
 }
 __device__ __forceinline__ void store_through(void* p, vec16 v) {
   asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(v));

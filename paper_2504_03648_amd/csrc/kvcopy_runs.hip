@@ -59,7 +59,8 @@ __global__ __launch_bounds__(kRunThreads) void kv_copy_runs_kernel(RunCopyArgs a
     const vec16 v = __builtin_nontemporal_load(in_pool);
     asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(in_stage), "v"(v) : "memory");
   } else {
-    __builtin_nontemporal_store(__builtin_nontemporal_load(in_stage), in_pool);
+    const vec16 v = __builtin_nontemporal_load(in_stage);
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt" ::"v"(in_pool), "v"(v) : "memory");
   }
 }
 
