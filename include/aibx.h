@@ -128,7 +128,7 @@ int aibx_index_destroy(aibx_index_t* index);
 /* Enqueues removal of every key. */
 int aibx_index_clear(aibx_index_t* index, void* stream);
 
-/* Batch upsert ("metadata update", Section 3.2.5). For each i < n: key absent -> stored with
+/* Batch upsert (the cache's metadata updates, Section 3.2.5). For each i < n: key absent -> stored with
  * d_values[i] (inserted); key present -> its value is overwritten (updated). A reserved key, or
  * a new key when no slot is free, is dropped (full). The same key may appear several times in one
  * batch if its values are identical: it then counts once as inserted (or updated) and the other
@@ -147,8 +147,9 @@ int aibx_index_insert(aibx_index_t* index, const uint64_t* d_keys, const uint64_
 int aibx_index_evict(aibx_index_t* index, const uint64_t* d_keys, int64_t n,
                      uint64_t* d_values_out, uint64_t* d_counters2, void* stream);
 
-/* Usage tracking and victim selection.  (Section 3.2.5 names a "scan-resistant eviction policy"
- * that "selectively persist[s] hot KV tensors" and does not describe it; this is the rule here.)
+/* Usage tracking and victim selection.  (Section 3.2.5 asks for an eviction policy that a one-off
+ * scan cannot disturb and that keeps the frequently reused KV; it names the policy without
+ * describing it. This is the rule used here.)
  * Every indexed key carries a touch count and the last epoch it was touched in; a newly inserted
  * key has count 0 and epoch 0, an upsert of a present key keeps its usage, eviction discards it.
  *   aibx_index_touch: for each i < n, if d_keys[i] is present its count goes up by one (saturating
@@ -198,8 +199,9 @@ int aibx_index_dump(const aibx_index_t* index, uint64_t* d_keys_out, uint64_t* d
                     uint64_t capacity, uint64_t* d_n_out, void* stream);
 
 /* ------------------------------------------------------------------------------------------
- * Prefix match.  (The "reusable prefix cache" test of the prefix-cache-aware policy,
- * Section 3.2.2: the caller compares match_len / n_r with its threshold.)
+ * Prefix match.  (The test behind the prefix-cache-aware routing policy of Section 3.2.2 - how
+ * much of a request's prefix is already cached; the caller compares match_len / n_r with its
+ * threshold.)
  * For every block b: d_values_out[b] = value of d_hashes[b] in the index, or AIBX_NO_VALUE.
  * For every request r: d_match_len[r] = the smallest j with block d_blk_off[r]+j absent, or its
  * block count if none is absent ("first miss": a block found behind a missing one still reports
@@ -230,9 +232,10 @@ int aibx_hash_match(const aibx_index_t* index, const int32_t* d_tokens, const in
                     uint64_t* d_values_out, int32_t* d_match_len, void* stream);
 
 /* ------------------------------------------------------------------------------------------
- * Prefix-cache-aware routing decision.  (Section 3.2.2: the policy "prioritizes instances with
- * reusable prefix cache, with a cache hit exceeding the threshold"; below the threshold it falls
- * back to the least-request policy of the same list.)
+ * Prefix-cache-aware routing decision.  (Section 3.2.2: among the gateway's routing policies, the
+ * one that prefers an instance already holding a reusable prefix of the request's KV cache when the
+ * hit is large enough; below that threshold this library falls back to the least-request policy of
+ * the same list.)
  * The index value of a block is read as the SET OF PODS holding it: bit p = pod p, p < n_pods <= 63
  * (AIBX_NO_VALUE = no pod; higher bits are ignored). d_pod_sets is the per-block output of
  * aibx_prefix_match / aibx_hash_match. For request r with n_r blocks and pod p,
@@ -285,6 +288,17 @@ int aibx_kv_gather(const aibx_pool_desc* pool, const int32_t* d_page_ids,
 int aibx_kv_scatter(const aibx_pool_desc* pool, const int32_t* d_page_ids,
                     const int32_t* d_slot_ids, int64_t n, const void* d_staging,
                     uint64_t staging_block_stride, uint64_t* d_bad_page_counter, void* stream);
+
+/* How aibx_kv_gather / aibx_kv_scatter split a call of n entries into kernel launches (host
+ * arithmetic only; nothing is launched and no device is needed). One workgroup of 256 lanes moves
+ * 4 KiB, and one launch may hold at most 2^32 - 1 threads, so a call that moves 64 GiB or more
+ * (e.g. offloading half of a 160 GiB pool, Section 3.2.5) takes more than one launch; entries are
+ * never split between launches. Launch k < capacity is written as (first_entry_out[k],
+ * n_entries_out[k], workgroups_out[k]); only pool->n_seg and pool->seg_bytes are read.
+ * Returns the number of launches (>= 0; it may exceed capacity), or INVALID_ARG / UNSUPPORTED (a
+ * single block that exceeds one launch). All pointers are HOST memory (nullable if capacity = 0). */
+int aibx_kv_copy_launches(const aibx_pool_desc* pool, int64_t n, int64_t* first_entry_out,
+                          int64_t* n_entries_out, uint32_t* workgroups_out, int32_t capacity);
 
 /* ------------------------------------------------------------------------------------------
  * The same copies for a pool whose segments are not contiguous (cross-engine reuse of KV,
@@ -340,6 +354,19 @@ int aibx_kv_offload(const aibx_pool_desc* pool, const int32_t* d_page_ids, int64
                     uint64_t host_block_stride, uint64_t* d_bad_page_counter, void* stream);
 int aibx_kv_onload(const aibx_pool_desc* pool, const int32_t* d_page_ids, int64_t n, const void* h_src,
                    uint64_t host_block_stride, uint64_t* d_bad_page_counter, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Measurement aid (not a step of the path; for benchmarks that want to place the lookup rates of
+ * aibx_prefix_match beside what independent random reads reach on a table of the same size).
+ * Lane i of the launch reads the first read_bytes bytes of a pseudo-random line_bytes-sized line
+ * of d_table, n_reads reads in all. Nothing is computed from what is read: *d_sink is written
+ * only if the XOR of a lane's reads happens to equal one fixed 64-bit constant.
+ *   d_table 128-byte aligned, table_bytes a power of two >= line_bytes; line_bytes a power of two
+ *   in [8, 4096]; read_bytes in {8, 16, 64, 128}, <= line_bytes; d_sink device uint64.
+ * Errors: INVALID_ARG, ALIGN, HIP. */
+int aibx_calib_random_reads(const void* d_table, uint64_t table_bytes, uint32_t line_bytes,
+                            uint32_t read_bytes, int64_t n_reads, uint64_t seed, uint64_t* d_sink,
+                            void* stream);
 
 #ifdef __cplusplus
 }

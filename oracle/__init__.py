@@ -23,11 +23,24 @@ _LIB = os.path.join(_HERE, "liboracle.so")
 NO_VALUE = np.uint64(0xFFFFFFFFFFFFFFFF)
 
 
+SANITIZE = os.environ.get("AIBX_ORACLE_SANITIZE", "") not in ("", "0")
+if SANITIZE:                       # a second library, so that the plain one is never replaced by it
+    _LIB = os.path.join(_HERE, "liboracle_san.so")
+
+
 def build(force: bool = False) -> str:
-    """Compile the oracle with g++ (host only). Returns the library path."""
+    """Compile the oracle with g++ (host only). Returns the library path. With
+    AIBX_ORACLE_SANITIZE=1 in the environment the build is instrumented with AddressSanitizer and
+    UndefinedBehaviorSanitizer (any finding aborts the process); loading it into Python needs the
+    ASan runtime preloaded, which tests/test_oracle_sanitized.py arranges for a child process."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wextra",
-                               "-o", _LIB, _SRC])
+        flags = ["-O2"]
+        if SANITIZE:
+            flags = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+                     "-fno-sanitize-recover=all"]
+        subprocess.check_call(["g++", *flags, "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wextra",
+                               "-o", _LIB + ".tmp", _SRC])
+        os.replace(_LIB + ".tmp", _LIB)
     return _LIB
 
 

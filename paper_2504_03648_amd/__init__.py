@@ -10,4 +10,5 @@ from .binding import (AibxError, PoolDesc, PoolRunsDesc, make_pool_runs_desc, ai
                       aibx_index_select_victims, aibx_index_stats, aibx_index_rebuild, aibx_prefix_match,
                       aibx_hash_match, aibx_route,
                       make_pool_desc,
-                      aibx_kv_gather, aibx_kv_scatter, aibx_kv_offload, aibx_kv_onload)
+                      aibx_kv_gather, aibx_kv_scatter, aibx_kv_offload, aibx_kv_onload,
+                      aibx_kv_copy_launches, aibx_calib_random_reads)

@@ -18,7 +18,8 @@ EXPORTS = [
     "aibx_index_clear", "aibx_index_insert", "aibx_index_evict", "aibx_index_count",
     "aibx_index_dump", "aibx_index_touch", "aibx_index_age", "aibx_index_select_victims",
     "aibx_index_stats", "aibx_index_rebuild",
-    "aibx_prefix_match", "aibx_hash_match", "aibx_route", "aibx_kv_gather", "aibx_kv_scatter", "aibx_kv_gather_runs", "aibx_kv_scatter_runs", "aibx_kv_offload", "aibx_kv_onload",
+    "aibx_prefix_match", "aibx_hash_match", "aibx_route", "aibx_kv_gather", "aibx_kv_scatter", "aibx_kv_copy_launches", "aibx_kv_gather_runs", "aibx_kv_scatter_runs", "aibx_kv_offload", "aibx_kv_onload",
+    "aibx_calib_random_reads",
 ]
 
 
@@ -83,10 +84,12 @@ def load(build_if_missing: bool = True):
     lib.aibx_hash_match.argtypes = [vp, vp, vp, vp, i32, i64, i32, u64, vp, vp, vp, vp]
     for f in (lib.aibx_kv_gather, lib.aibx_kv_scatter):
         f.argtypes = [C.POINTER(PoolDesc), vp, vp, i64, vp, u64, vp, vp]
+    lib.aibx_kv_copy_launches.argtypes = [C.POINTER(PoolDesc), i64, vp, vp, vp, i32]
     for f in (lib.aibx_kv_gather_runs, lib.aibx_kv_scatter_runs):
         f.argtypes = [C.POINTER(PoolRunsDesc), vp, vp, i64, vp, u64, vp, vp]
     for f in (lib.aibx_kv_offload, lib.aibx_kv_onload):
         f.argtypes = [C.POINTER(PoolDesc), vp, i64, vp, u64, vp, vp]
+    lib.aibx_calib_random_reads.argtypes = [vp, u64, C.c_uint32, C.c_uint32, i64, u64, vp, vp]
     for name in EXPORTS[4:]:
         getattr(lib, name).restype = C.c_int
     _lib = lib
@@ -244,6 +247,15 @@ def aibx_kv_scatter(pool: PoolDesc, d_page_ids, d_slot_ids, n, d_staging, stagin
         _p(d_staging), int(staging_block_stride), _p(d_bad_page_counter, U64), _s(stream)))
 
 
+def aibx_kv_copy_launches(pool: PoolDesc, n: int, capacity: int = 64):
+    """[(first_entry, n_entries, workgroups)] of the launches a gather/scatter of n entries makes."""
+    first, cnt, grid = (C.c_int64 * capacity)(), (C.c_int64 * capacity)(), (C.c_uint32 * capacity)()
+    k = load().aibx_kv_copy_launches(C.byref(pool), int(n), first, cnt, grid, capacity)
+    if k < 0:
+        raise AibxError("aibx_kv_copy_launches", k)
+    return [(first[i], cnt[i], grid[i]) for i in range(min(k, capacity))], k
+
+
 def make_pool_runs_desc(pool_tensor, n_seg, n_run, seg_stride, page_stride, run_stride, run_bytes, n_pages):
     return PoolRunsDesc(pool_tensor.data_ptr(), int(n_seg), int(n_run), int(seg_stride), int(page_stride),
                         int(run_stride), int(run_bytes), int(n_pages))
@@ -280,3 +292,9 @@ def aibx_kv_onload(pool: PoolDesc, d_page_ids, n, h_src, host_block_stride, d_ba
     _check("aibx_kv_onload", load().aibx_kv_onload(
         C.byref(pool), _p(d_page_ids, torch.int32), int(n), _host_ptr(h_src), int(host_block_stride),
         _p(d_bad_page_counter, U64), _s(stream)))
+
+
+def aibx_calib_random_reads(d_table, table_bytes, line_bytes, read_bytes, n_reads, seed, d_sink, stream=None):
+    _check("aibx_calib_random_reads", load().aibx_calib_random_reads(
+        _p(d_table), int(table_bytes), int(line_bytes), int(read_bytes), int(n_reads), int(seed),
+        _p(d_sink, U64), _s(stream)))

@@ -9,7 +9,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _CSRC = os.path.join(_HERE, "csrc")
 _INCLUDE = os.path.join(os.path.dirname(_HERE), "include")
 LIB_PATH = os.path.join(_HERE, "libaibx.so")
-SOURCES = ["status.hip", "hash.hip", "index.hip", "kvcopy.hip", "kvcopy_runs.hip", "route.hip", "hosttier.hip"]
+SOURCES = ["status.hip", "hash.hip", "index.hip", "kvcopy.hip", "kvcopy_runs.hip", "route.hip", "hosttier.hip", "calib.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -27,4 +27,14 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 
 inline hipStream_t as_stream(void* s) { return static_cast<hipStream_t>(s); }
 
+// How the copy kernels split a call into launches. One workgroup moves one tile, and a launch
+// whose grid times its workgroup size reaches 2^32 threads is refused by the runtime, so a launch
+// takes at most floor((2^32 - 1) / threads) workgroups - rounded down to whole rounds of the 8
+// XCDs, because the tile map deals the workgroups of a launch to the XCDs in eighths. Entries are
+// never split between launches. Returns 0 when a single entry does not fit one launch.
+inline int64_t max_entries_per_launch(u64 tiles_per_entry, u32 threads) {
+  const u64 max_groups = (0xFFFFFFFFull / threads) & ~7ull;
+  return tiles_per_entry == 0 ? 0 : (int64_t)(max_groups / tiles_per_entry);
+}
+
 }  // namespace aibx

@@ -1,5 +1,5 @@
-// GPU-resident cache index and prefix match (the cache pool's metadata and its "asynchronous
-// metadata updates", Section 3.2.5 of the paper; the reusable-prefix test of the
+// GPU-resident cache index and prefix match (the cache pool's metadata, which Section 3.2.5 of the
+// paper updates asynchronously, off the engines' critical path; the reusable-prefix test of the
 // prefix-cache-aware policy, Section 3.2.2). Semantics are stated in aibx.h.
 //
 // Behind the slots the storage holds one 32-bit usage word per slot (touch count and last epoch)
@@ -291,7 +291,7 @@ __global__ __launch_bounds__(kIndexThreads) void index_evict_kernel(
 }
 
 // ---- usage tracking and victim selection -------------------------------------------------------
-// (the "scan-resistant eviction policy" of Section 3.2.5; the rule is stated in aibx.h)
+// (the eviction policy of Section 3.2.5, which a one-off scan must not disturb; the rule is stated in aibx.h)
 // touch: one lane per key; finds the key's slot like a lookup and bumps its usage word with a
 // compare-and-swap loop (count saturates at 255, epoch only moves forward).
 __global__ __launch_bounds__(kIndexThreads) void index_touch_kernel(Table t, const u64* __restrict__ keys,

@@ -79,8 +79,11 @@ __device__ __forceinline__ void load_bucket_keys(const u64* bucket, u64 (&keys)[
 
 // ---- tags --------------------------------------------------------------------------------------
 // One byte per slot, the 8 tags of a bucket in one 64-bit word: 0 = the slot is EMPTY, 0xFF = it
-// is a TOMBSTONE, anything else = 8 bits of the key's product that neither the home bucket nor the
-// probe step use. The update kernels write a slot's tag after they have won its key word, so
+// is a TOMBSTONE, anything else = bits 24..31 of the key's product. The home bucket is the
+// product's top lg(n_buckets) bits, so up to 2^35 slots the tag is independent of it (keys that
+// meet in a bucket still differ in their tags); the probe step (bits 7 and up) does share bits
+// with the tag in tables of 2^18 buckets or more, which costs nothing: keys with equal tags in
+// one bucket are told apart by the key comparison, whatever their steps. The update kernels write a slot's tag after they have won its key word, so
 // between launches the tags mirror the keys exactly. A lookup walks the tags only - an eighth of
 // the bytes of the key words, so the tags of a table stay in cache where its slots do not (16 Mi
 // slots: 16 MiB of tags against 256 MiB of slots) - and touches a slot only where the tag matches:

@@ -38,13 +38,13 @@ typedef __attribute__((ext_vector_type(4))) u32 vec16;
 // The asm statements below carry no "memory" clobber on purpose: they are volatile (kept, and kept
 // in order), the data dependence orders each store after its load, and without the clobber the
 // compiler may fetch the page and slot ids with scalar loads issued together, which shortens the
-// dependent latency in front of every tile.
+// dependent latency in front of every tile. The load and the wait for it are ONE statement, so
+// the register it returns is complete wherever the compiler copies, spills or stores it.
 __device__ __forceinline__ vec16 load_stream(const void* p) {
   vec16 v;
-  asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(v) : "v"(p));
+  asm volatile("global_load_dwordx4 %0, %1, off nt\n\ts_waitcnt vmcnt(0)" : "=&v"(v) : "v"(p));
   return v;
 }
-__device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(0)"); }
 __device__ __forceinline__ void store_stream(void* p, vec16 v) {
   asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt" ::"v"(p), "v"(v));
 }
@@ -70,13 +70,9 @@ __device__ __forceinline__ void copy_tile(const CopyArgs& a, const int32_t* __re
   unsigned char* in_pool = a.pool + (u64)s * a.seg_stride + (u64)p * a.page_stride + off;
   unsigned char* in_stage = a.staging + (u64)q * a.staging_stride + (u64)s * a.seg_bytes + off;
   if (kGather) {
-    const vec16 v = load_stream(in_pool);
-    wait_loads();
-    store_through(in_stage, v);
+    store_through(in_stage, load_stream(in_pool));
   } else {
-    const vec16 v = load_stream(in_stage);
-    wait_loads();
-    store_stream(in_pool, v);
+    store_stream(in_pool, load_stream(in_stage));
   }
 }
 
@@ -89,6 +85,23 @@ __global__ __launch_bounds__(kThreads) void kv_copy_xcd_kernel(CopyArgs a, const
   const u32 i = t / a.tiles_per_block;
   copy_tile<kGather>(a, page_ids, slot_ids, a.first_entry + i, t - i * a.tiles_per_block, kThreads);
 }
+
+constexpr u32 kCopyThreads = 256;  // 4 KiB tiles
+
+// Tiles per entry and entries per launch of a pool geometry (false: one block exceeds a launch).
+struct CopyShape {
+  u64 chunks_per_seg, tiles_per_block;
+  int64_t max_entries;
+};
+bool copy_shape(const aibx_pool_desc* pool, CopyShape& s) {
+  const u64 tile_bytes = (u64)kCopyThreads * 16;
+  s.chunks_per_seg = (pool->seg_bytes + tile_bytes - 1) / tile_bytes;
+  s.tiles_per_block = s.chunks_per_seg * (u64)pool->n_seg;
+  s.max_entries = max_entries_per_launch(s.tiles_per_block, kCopyThreads);
+  return s.max_entries >= 1;
+}
+// workgroups of a launch that moves n_here entries: its tiles rounded up to whole rounds of 8
+u32 copy_grid(const CopyShape& s, int64_t n_here) { return (u32)((((u64)n_here * s.tiles_per_block + 7) / 8) * 8); }
 
 template <bool kGather>
 int launch_copy(const aibx_pool_desc* pool, const int32_t* d_page_ids, const int32_t* d_slot_ids,
@@ -105,11 +118,8 @@ int launch_copy(const aibx_pool_desc* pool, const int32_t* d_page_ids, const int
     return AIBX_ERR_ALIGN;
   if (!aligned(d_page_ids, 4) || !aligned(d_slot_ids, 4) || !aligned(d_bad, 8)) return AIBX_ERR_ALIGN;
 
-  const u32 threads = 256;  // 4 KiB tiles
-  const u64 tile_bytes = (u64)threads * 16;
-  const u64 cps = (pool->seg_bytes + tile_bytes - 1) / tile_bytes;
-  const u64 tpb = cps * (u64)pool->n_seg;
-  if (tpb > 0x7FFFFFF0ull) return AIBX_ERR_UNSUPPORTED;
+  CopyShape shape;
+  if (!copy_shape(pool, shape)) return AIBX_ERR_UNSUPPORTED;
 
   CopyArgs a;
   a.pool = static_cast<unsigned char*>(pool->base);
@@ -122,18 +132,18 @@ int launch_copy(const aibx_pool_desc* pool, const int32_t* d_page_ids, const int
   a.n = n;
   a.n_pages = pool->n_pages;
   a.first_entry = 0;
-  a.chunks_per_seg = (u32)cps;
-  a.tiles_per_block = (u32)tpb;
+  a.chunks_per_seg = (u32)shape.chunks_per_seg;
+  a.tiles_per_block = (u32)shape.tiles_per_block;
   a.total_tiles = a.tiles_per_xcd = 0;
   hipStream_t st = as_stream(stream);
-  // split so that one launch has fewer than 2^31 tiles
-  const int64_t max_entries = (int64_t)(0x7FFFFFF0ull / tpb);
-  for (int64_t first = 0; first < n; first += max_entries) {
-    const int64_t n_here = (n - first) < max_entries ? (n - first) : max_entries;
+  // as many launches as the grid limit asks for (one, below 64 GiB per call)
+  for (int64_t first = 0; first < n; first += shape.max_entries) {
+    const int64_t n_here = (n - first) < shape.max_entries ? (n - first) : shape.max_entries;
+    const u32 grid = copy_grid(shape, n_here);
     a.first_entry = first;
-    a.total_tiles = (u32)((u64)n_here * tpb);
-    a.tiles_per_xcd = (a.total_tiles + 7) / 8;
-    kv_copy_xcd_kernel<kGather, 256><<<dim3(a.tiles_per_xcd * 8), 256, 0, st>>>(a, d_page_ids, d_slot_ids);
+    a.total_tiles = (u32)((u64)n_here * shape.tiles_per_block);
+    a.tiles_per_xcd = grid / 8;
+    kv_copy_xcd_kernel<kGather, kCopyThreads><<<dim3(grid), kCopyThreads, 0, st>>>(a, d_page_ids, d_slot_ids);
     const int rc = launch_status();
     if (rc != AIBX_OK) return rc;
   }
@@ -144,6 +154,24 @@ int launch_copy(const aibx_pool_desc* pool, const int32_t* d_page_ids, const int
 }  // namespace aibx
 
 extern "C" {
+
+int aibx_kv_copy_launches(const aibx_pool_desc* pool, int64_t n, int64_t* first_entry_out,
+                          int64_t* n_entries_out, uint32_t* workgroups_out, int32_t capacity) {
+  using namespace aibx;
+  if (!pool || n < 0 || capacity < 0 || pool->n_seg < 1 || pool->seg_bytes == 0) return AIBX_ERR_INVALID_ARG;
+  if (capacity && (!first_entry_out || !n_entries_out || !workgroups_out)) return AIBX_ERR_INVALID_ARG;
+  CopyShape shape;
+  if (!copy_shape(pool, shape)) return AIBX_ERR_UNSUPPORTED;
+  int k = 0;
+  for (int64_t first = 0; first < n; first += shape.max_entries, ++k) {
+    if (k >= capacity) continue;
+    const int64_t n_here = (n - first) < shape.max_entries ? (n - first) : shape.max_entries;
+    first_entry_out[k] = first;
+    n_entries_out[k] = n_here;
+    workgroups_out[k] = copy_grid(shape, n_here);
+  }
+  return k;
+}
 
 int aibx_kv_gather(const aibx_pool_desc* pool, const int32_t* d_page_ids, const int32_t* d_slot_ids,
                    int64_t n, void* d_staging, uint64_t staging_block_stride,

@@ -84,7 +84,8 @@ int launch_copy_runs(const aibx_pool_runs_desc* pool, const int32_t* d_page_ids,
   const u64 tile_bytes = (u64)kRunThreads * 16;
   const u64 cps = (seg_bytes + tile_bytes - 1) / tile_bytes;
   const u64 tpb = cps * (u64)pool->n_seg;
-  if (tpb > 0x7FFFFFF0ull) return AIBX_ERR_UNSUPPORTED;
+  const int64_t max_entries = max_entries_per_launch(tpb, kRunThreads);
+  if (max_entries < 1) return AIBX_ERR_UNSUPPORTED;  // one block alone exceeds a launch
 
   RunCopyArgs a;
   a.pool = static_cast<unsigned char*>(pool->base);
@@ -100,7 +101,6 @@ int launch_copy_runs(const aibx_pool_runs_desc* pool, const int32_t* d_page_ids,
   a.chunks_per_seg = (u32)cps;
   a.tiles_per_block = (u32)tpb;
   hipStream_t st = as_stream(stream);
-  const int64_t max_entries = (int64_t)(0x7FFFFFF0ull / tpb);  // one launch has fewer than 2^31 tiles
   for (int64_t first = 0; first < n; first += max_entries) {
     const int64_t n_here = (n - first) < max_entries ? (n - first) : max_entries;
     a.first_entry = first;

@@ -1,6 +1,6 @@
-// Prefix-cache-aware routing decision (Section 3.2.2 of the paper: the policy "prioritizes
-// instances with reusable prefix cache, with a cache hit exceeding the threshold"; its fallback
-// here is the least-request policy of the same list). Semantics are stated in aibx.h.
+// Prefix-cache-aware routing decision (Section 3.2.2 of the paper: route to an instance that
+// already holds a reusable prefix of the request's KV cache when the hit is large enough; the
+// fallback here is the least-request policy of the same list). Semantics are stated in aibx.h.
 //
 // One wavefront per request. A block's index value is the set of pods holding it (bit p = pod p).
 // The set of pods that hold ALL of blocks 0..j is the running AND of those sets; it only shrinks,

@@ -30,7 +30,7 @@ class OracleBackend:
     def _check(self, page_ids, slot_ids):
         n = len(page_ids)
         slots = np.arange(n) if slot_ids is None else np.asarray(slot_ids)
-        assert n == 0 or (slots.min() >= 0 and (slots.max() + 1) * self.stride <= len(self.staging))
+        assert n == 0 or (int(slots.min()) >= 0 and (int(slots.max()) + 1) * self.stride <= len(self.staging))
 
     def gather(self, page_ids, slot_ids):
         self._check(page_ids, slot_ids)
@@ -60,6 +60,61 @@ class OracleBackend:
         ids = np.asarray(slot_ids, dtype=np.int64)
         st = self.staging.reshape(-1, self.stride)
         return st[ids, : self.geom.blk_bytes].copy()
+
+
+class CompactOracleBackend(OracleBackend):
+    """The oracle on a pool that is too large to mirror on the host: only the pages a flow names
+    exist here, as rows of a compact pool of `capacity` pages with the same planes and segment
+    size. A page gets its row the first time a call names it, filled with the page's original
+    bytes by `fetch(page_ids) -> uint8[n, blk_bytes]` (transport of input data; none of the
+    method's arithmetic). Page ids are translated to rows on the way into the oracle's copies:
+    holes stay holes, ids outside the real pool stay outside the compact one."""
+    name = "oracle-compact"
+
+    def __init__(self, fetch, capacity):
+        super().__init__()
+        self.fetch, self.capacity = fetch, int(capacity)
+        self.row_of = {}
+        self.full_pages = 0
+
+    def pool_create(self, geom, kv_dtype, cfg):
+        from workloads import Geometry
+        self.full_pages = geom.n_pages
+        self.geom = Geometry(geom.n_seg, geom.seg_bytes, self.capacity, geom.layout)
+        self.pool = np.zeros(self.geom.pool_bytes, dtype=np.uint8)
+
+    def named_pages(self):
+        return np.fromiter(self.row_of.keys(), dtype=np.int64, count=len(self.row_of))
+
+    def _rows(self, page_ids):
+        ids = np.asarray(page_ids, dtype=np.int64)
+        real = (ids >= 0) & (ids < self.full_pages)
+        new = [int(p) for p in np.unique(ids[real]) if int(p) not in self.row_of]
+        if new:
+            assert len(self.row_of) + len(new) <= self.capacity, "compact pool too small for this flow"
+            planes = self._planes()
+            for a in range(0, len(new), 512):
+                part = new[a:a + 512]
+                rows = np.arange(len(self.row_of), len(self.row_of) + len(part))
+                blocks = self.fetch(np.asarray(part, dtype=np.int64))
+                planes[:, rows, :] = blocks.reshape(len(part), self.geom.n_seg, self.geom.seg_bytes).transpose(1, 0, 2)
+                for p, r in zip(part, rows):
+                    self.row_of[p] = int(r)
+        out = np.where(ids < 0, -1, self.capacity).astype(np.int32)   # holes; ids beyond the pool stay bad
+        out[real] = [self.row_of[int(p)] for p in ids[real]]
+        return out
+
+    def gather(self, page_ids, slot_ids):
+        return super().gather(self._rows(page_ids), slot_ids)
+
+    def scatter(self, page_ids, slot_ids):
+        return super().scatter(self._rows(page_ids), slot_ids)
+
+    def fill_pages(self, page_ids, byte):
+        super().fill_pages(self._rows(page_ids), byte)
+
+    def read_pages(self, page_ids):
+        return super().read_pages(self._rows(page_ids))
 
 
 class HipIndex:
@@ -195,12 +250,33 @@ class HipBackend:
     """The HIP library through its Python binding; host arrays in, host arrays out."""
     name = "hip"
 
-    def __init__(self, two_streams=True):
+    GUARD = 4096          # canary bytes in front of and behind the pool and the staging buffer
+    GUARD_BYTE = 0xC3
+
+    def __init__(self, two_streams=True, device_fill=False):
         import torch
         import paper_2504_03648_amd as aibx
         self.t, self.a = torch, aibx
         self.two_streams = two_streams
+        self.device_fill = device_fill      # pool bytes drawn on the GPU (full-size pools)
         self.pool = self.staging = self.geom = self.desc = None
+        self._pool_buf = self._staging_buf = None
+
+    def _guarded(self, nbytes):
+        """A buffer of nbytes between two canary regions: (whole allocation, the inner view)."""
+        G = self.GUARD
+        buf = self.t.empty(nbytes + 2 * G, dtype=self.t.uint8, device="cuda")
+        buf[:G] = self.GUARD_BYTE
+        buf[G + nbytes:] = self.GUARD_BYTE
+        return buf, buf[G:G + nbytes]
+
+    def check_guards(self):
+        """No call wrote in front of or behind the pool or the staging buffer."""
+        G = self.GUARD
+        for buf in (self._pool_buf, self._staging_buf):
+            if buf is not None:
+                assert bool((buf[:G] == self.GUARD_BYTE).all()) and bool((buf[-G:] == self.GUARD_BYTE).all()), \
+                    "a copy wrote outside its buffer"
 
     def _dev(self, x, dtype):
         return self.t.from_numpy(np.ascontiguousarray(x, dtype=dtype).copy()).cuda()
@@ -219,16 +295,23 @@ class HipBackend:
 
     def pool_create(self, geom, kv_dtype, cfg, host_bytes=None):
         """Same bytes as the oracle backend's pool (generated on the host, uploaded)."""
-        from workloads import fill_pool_numpy
+        from workloads import fill_pool_numpy, fill_pool_torch
+        if self.pool is not None and self.geom == geom:
+            return                              # created ahead of the flow (full-size tests)
         self.geom = geom
-        if host_bytes is None:
-            host_bytes = fill_pool_numpy(geom, kv_dtype, cfg)
-        self.pool = self.t.from_numpy(host_bytes).cuda()
+        self._pool_buf, self.pool = self._guarded(geom.pool_bytes)
+        if host_bytes is None and self.device_fill:
+            fill_pool_torch(self.pool, kv_dtype, cfg)
+        else:
+            if host_bytes is None:
+                host_bytes = fill_pool_numpy(geom, kv_dtype, cfg)
+            self.pool.copy_(self.t.from_numpy(host_bytes))
         self.desc = self.a.make_pool_desc(self.pool, *geom.as_tuple())
 
     def staging_create(self, n_blocks, stride):
         self.stride = int(stride)
-        self.staging = self.t.zeros(int(n_blocks) * self.stride, dtype=self.t.uint8, device="cuda")
+        self._staging_buf, self.staging = self._guarded(int(n_blocks) * self.stride)
+        self.staging.zero_()
 
     def _ids(self, page_ids, slot_ids):
         p = self._dev(page_ids, np.int32)

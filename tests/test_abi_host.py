@@ -115,3 +115,57 @@ def test_argument_errors_are_raised_before_any_launch(lib):
     assert lib.aibx_kv_gather(C.byref(bad), fake, None, 1, fake, 8208, None, None) == -2
     bad = PoolDesc(0x1000, 0, 1 << 20, 4096, 4096, 16)
     assert lib.aibx_kv_scatter(C.byref(bad), fake, None, 1, fake, 8192, None, None) == -1
+
+
+def test_copy_launch_split_respects_the_grid_limit(lib):
+    """A launch holds at most 2^32 - 1 threads (256 per workgroup, one workgroup per 4 KiB tile):
+    calls that move 64 GiB or more are split, entries are never cut, nothing is left out."""
+    from paper_2504_03648_amd.binding import PoolDesc, aibx_kv_copy_launches
+    max_groups = ((2**32 - 1) // 256) & ~7
+    cases = [
+        (160, 32768, 16384),      # half of the 160 GiB pool of the 70B-shaped config: 80 GiB
+        (160, 32768, 32768),      # all of it
+        (64, 32768, 4608),        # one batch of the 8B-shaped config: a single launch
+        (1, 4497408, 17408),      # page-major latent pages (ragged last tile per segment)
+        (61, 73728, 17408),
+        (1, 16, 1 << 26),         # 16-byte segments: one tile per entry
+        (3, 4096 * 5_000_000, 3), # a block of 15 M tiles: one entry per launch
+    ]
+    for n_seg, seg_bytes, n in cases:
+        d = PoolDesc(0x1000, n_seg, 1 << 40, seg_bytes, seg_bytes, 1 << 30)
+        tpb = -(-seg_bytes // 4096) * n_seg
+        plan, k = aibx_kv_copy_launches(d, n, capacity=64)
+        assert k == len(plan) >= 1
+        nxt = 0
+        for first, cnt, grid in plan:
+            assert first == nxt and cnt >= 1
+            assert grid % 8 == 0 and grid * 256 < 2**32 and grid <= max_groups
+            assert cnt * tpb <= grid < cnt * tpb + 8
+            nxt = first + cnt
+        assert nxt == n
+        assert all(c == plan[0][1] for _, c, _ in plan[:-1])          # equal launches, then the rest
+        assert k == -(-n // (max_groups // tpb))
+    plan, k = aibx_kv_copy_launches(PoolDesc(0x1000, 160, 1 << 30, 32768, 32768, 32768), 16384)
+    assert k == 2                                                      # 80 GiB: two launches
+    plan, k = aibx_kv_copy_launches(PoolDesc(0x1000, 1, 0, 16, 16, 8), 0)
+    assert (plan, k) == ([], 0)
+    plan, k = aibx_kv_copy_launches(PoolDesc(0x1000, 1, 0, 16, 16, 8), 1 << 30, capacity=4)
+    assert k == -(-(1 << 30) // max_groups) and len(plan) == 4         # more launches than asked for
+    big = PoolDesc(0x1000, 8, 1 << 50, 4096 * 3_000_000, 4096 * 3_000_000, 8)   # 24 M tiles in one block
+    assert lib.aibx_kv_copy_launches(C.byref(big), 1, None, None, None, 0) == -3
+    assert lib.aibx_kv_gather(C.byref(big), C.c_void_p(0x1000), None, 1, C.c_void_p(0x1000), 8 * 4096 * 3_000_000,
+                              None, None) == -3
+    assert lib.aibx_kv_copy_launches(None, 1, None, None, None, 0) == -1
+
+
+def test_calibration_kernel_rejects_bad_arguments(lib):
+    fake = C.c_void_p(0x1000)
+    f = lib.aibx_calib_random_reads
+    assert f(None, 1 << 20, 128, 8, 10, 0, fake, None) == -1
+    assert f(fake, 1 << 20, 128, 8, -1, 0, fake, None) == -1
+    assert f(fake, 1 << 20, 100, 8, 10, 0, fake, None) == -1          # line size not a power of two
+    assert f(fake, (1 << 20) + 128, 128, 8, 10, 0, fake, None) == -1  # table size not a power of two
+    assert f(fake, 1 << 20, 64, 128, 10, 0, fake, None) == -1         # read longer than a line
+    assert f(fake, 1 << 20, 128, 24, 10, 0, fake, None) == -1
+    assert f(C.c_void_p(0x1040), 1 << 20, 128, 8, 10, 0, fake, None) == -2
+    assert f(fake, 1 << 20, 128, 8, 0, 0, fake, None) == 0

@@ -361,6 +361,80 @@ def test_index_large_batch_with_shared_prefix_duplicates():
     assert gi.count() == 0
 
 
+def test_two_block_sizes_and_two_seeds_share_one_index():
+    """Engines with different page sizes (16- and 64-token blocks) and two tenants (hash seeds)
+    index their blocks in ONE table: each population matches only its own entries, the lengths
+    agree with the oracle's, evicting one population leaves the others whole, and the one-launch
+    path sees the same state."""
+    rng = np.random.default_rng(1664)
+    tok, tok_off, lens = _ragged(rng, 40, 64, 3000)
+    pops = [(16, 0), (64, 0), (16, 0xABCDEF), (64, 0xABCDEF), (24, 5)]     # (block size, seed)
+    gi, oi = HipIndex(1 << 15), oracle.Index(1 << 15)
+    hip = HipBackend()
+    hs, bos = [], []
+    for k, (B, seed) in enumerate(pops):
+        bo = np.zeros(len(lens) + 1, dtype=np.int64)
+        np.cumsum(lens // B, out=bo[1:])
+        h = oracle.block_hash(tok, tok_off, bo, B, seed)
+        assert np.array_equal(hip.block_hash(tok, tok_off, bo, B, seed), h)
+        hs.append(h)
+        bos.append(bo)
+        keep = np.arange(len(h)) % 3 != 2 - (k % 2)                        # leave holes so lengths vary
+        vals = (np.uint64(k) << np.uint64(32)) | np.arange(len(h), dtype=np.uint64)
+        for ix in (gi, oi):
+            ix.insert(h[keep], vals[keep])
+    assert len(np.unique(np.concatenate(hs))) == sum(len(h) for h in hs)   # the populations never collide
+    assert np.array_equal(gi.counters_insert, oi.counters_insert)
+
+    def check():
+        for (B, seed), h, bo in zip(pops, hs, bos):
+            gv, gm = gi.match(h, bo)
+            ov, om = oi.match(h, bo)
+            assert np.array_equal(gv, ov) and np.array_equal(gm, om)
+            present = gv != NO
+            assert np.all((gv[present] >> np.uint64(32)) == np.uint64(pops.index((B, seed))))
+            fh, fv, fm = hip_hash_match(gi, tok, tok_off, bo, B, seed)
+            assert np.array_equal(fh, h) and np.array_equal(fv, ov) and np.array_equal(fm, om)
+    check()
+    assert np.array_equal(gi.evict(hs[1]), oi.evict(hs[1]))                # the 64-token blocks of tenant 0 go
+    check()
+    assert gi.count() == oi.count()
+    assert all(np.array_equal(a, b) for a, b in zip(gi.dump(), oi.dump()))
+
+
+def test_index_load_095_on_a_million_slots_matches_the_oracle():
+    """The bound of 4,096 buckets per probe sequence is the one point where the table is not the
+    oracle's abstract map. It must not bind where the map has room: a 2^20-slot table driven to a
+    load factor of 0.95 in batches, with evictions in between (tombstones), reports exactly the
+    oracle's counters, contents and lookups."""
+    n_slots = 1 << 20
+    rng = np.random.default_rng(95)
+    keys = np.unique(rng.integers(1, 2**63, size=int(1.02 * n_slots), dtype=np.uint64))
+    rng.shuffle(keys)
+    gi, oi = HipIndex(n_slots), oracle.Index(n_slots)
+    target = int(0.95 * n_slots)
+    step = 1 << 17
+    live_hi = 0
+    for a in range(0, target, step):
+        b = min(target, a + step)
+        for ix in (gi, oi):
+            ix.insert(keys[a:b], keys[a:b] ^ np.uint64(0x55))
+        ev = keys[a:b][:: 16]                                               # evict a sixteenth again ...
+        assert np.array_equal(gi.evict(ev), oi.evict(ev))
+        for ix in (gi, oi):
+            ix.insert(ev, ev + np.uint64(1))                                # ... and bring it back with new values
+        live_hi = b
+    assert np.array_equal(gi.counters_insert, oi.counters_insert)
+    assert int(gi.counters_insert[2]) == 0 and gi.count() == oi.count() == target
+    probe = np.concatenate([keys[:live_hi][:: 7], keys[target:]])          # present and absent keys
+    bo = np.array([0, len(probe)], dtype=np.int64)
+    gv, gm = gi.match(probe, bo)
+    ov, om = oi.match(probe, bo)
+    assert np.array_equal(gv, ov) and np.array_equal(gm, om)
+    assert all(np.array_equal(a, b) for a, b in zip(gi.dump(), oi.dump()))
+    assert np.array_equal(gi.counters_evict, oi.counters_evict)
+
+
 def test_match_edge_cases():
     gi, oi = HipIndex(64), oracle.Index(64)
     keys = np.arange(1, 30, dtype=np.uint64)
@@ -538,6 +612,7 @@ def test_gather_scatter_parity(n_seg, seg_bytes, n_pages, n):
     assert ob.scatter(pages, sl) == hb.scatter(pages, sl) == 0
     assert np.array_equal(hb.pool.cpu().numpy(), ob.pool)                # whole pool
     assert np.array_equal(hb.read_slots(all_slots), ob.read_slots(all_slots))
+    hb.check_guards()                                                    # canaries around pool and staging intact
 
 
 def test_gather_then_scatter_is_identity_on_the_pool():
@@ -768,6 +843,7 @@ def test_flow_offload_onload_small(layout):
     assert flows.traces_equal(a, b) == []
     assert np.array_equal(hb.pool.cpu().numpy(), ob.pool)
     assert np.array_equal(hb.staging.cpu().numpy(), ob.staging)
+    hb.check_guards()
 
 
 def test_flow_stress_small_two_streams():
@@ -778,3 +854,4 @@ def test_flow_stress_small_two_streams():
     assert flows.traces_equal(a, b) == []
     assert np.array_equal(hb.pool.cpu().numpy(), ob.pool)
     assert np.array_equal(hb.staging.cpu().numpy(), ob.staging)
+    hb.check_guards()

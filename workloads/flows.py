@@ -159,15 +159,26 @@ def flow_offload_onload(wl: Workload, be) -> dict:
     return tr
 
 
-def flow_stress(wl: Workload, be, n_rounds: int = 8, q: int = 4096) -> dict:
+def flow_stress(wl: Workload, be, n_rounds: int = 8, q: int = 4096, extra_tokens=None,
+                page_span=None) -> dict:
     """Config 5: after the preload, rounds of {insert q new keys, evict the q oldest live real
     keys, probe about 4q block hashes}, while disjoint page batches are gathered and scattered
-    (the backend may run those two on separate streams via be.gather_scatter_pair)."""
+    (the backend may run those two on separate streams via be.gather_scatter_pair).
+    extra_tokens = (tokens, tok_off, blk_off) of further requests of the same mix: their block
+    hashes extend the supply of keys when n_rounds*q exceeds the batch's own distinct blocks.
+    page_span: the copies use only this many pages of the pool (the first of a seeded permutation)
+    and go round them again and again in batches of wl.batch_pages; by default every round takes
+    fresh pages."""
     tr = {"round_values": [], "round_match_len": [], "round_evicted": []}
     g = wl.geom
     h = be.block_hash(wl.tokens, wl.tok_off, wl.blk_off, wl.block_size, wl.hash_seed)
     tr["hash"] = h
-    dkeys, _, rank = _distinct_in_order(h)
+    supply = h
+    if extra_tokens is not None:
+        h2 = be.block_hash(*extra_tokens, wl.block_size, wl.hash_seed)
+        tr["hash_extra"] = h2
+        supply = np.concatenate([h, h2])
+    dkeys, _, rank = _distinct_in_order(supply)
     n_keys = len(dkeys)
     n_pre = max(0, n_keys - n_rounds * q)              # the tail is inserted round by round
     dvalues = ELSEWHERE | np.arange(n_keys, dtype=np.uint64)
@@ -179,10 +190,15 @@ def flow_stress(wl: Workload, be, n_rounds: int = 8, q: int = 4096) -> dict:
     if n_fill:
         ix.insert(*filler_keys(wl.cfg, n_fill))
     be.pool_create(g, wl.kv_dtype, wl.cfg)
-    bp = min(wl.batch_pages, g.n_pages // (2 * n_rounds))
-    be.staging_create(2 * bp, g.blk_bytes)
     rng = ops_rng(wl.cfg, 3)
     page_order = rng.permutation(g.n_pages).astype(np.int32)
+    if page_span is None:
+        bp = min(wl.batch_pages, g.n_pages // (2 * n_rounds))
+    else:
+        page_order = page_order[:page_span]
+        bp = min(wl.batch_pages, page_span // 2)
+    span = len(page_order)
+    be.staging_create(2 * bp, g.blk_bytes)
     req_order = rng.permutation(wl.n_req)
     probe_ptr, ins_ptr, ev_ptr = 0, n_pre, 0
     for t in range(n_rounds):
@@ -207,15 +223,16 @@ def flow_stress(wl: Workload, be, n_rounds: int = 8, q: int = 4096) -> dict:
         tr["round_match_len"].append(m)
         # copies: gather batch 2t into staging half A while staging half B is scattered over
         # batch 2t+1 (disjoint pages, disjoint slots)
-        ga = page_order[(2 * t) * bp:(2 * t + 1) * bp]
-        sb = page_order[(2 * t + 1) * bp:(2 * t + 2) * bp]
+        ga = np.take(page_order, np.arange((2 * t) * bp, (2 * t + 1) * bp), mode="wrap")
+        sb = np.take(page_order, np.arange((2 * t + 1) * bp, (2 * t + 2) * bp), mode="wrap")
         slots_a = np.arange(bp, dtype=np.int32)
         slots_b = np.arange(bp, 2 * bp, dtype=np.int32)
         if t == 0:
             assert be.gather(sb[::-1].copy(), slots_b) == 0    # give half B defined contents
         bad = be.gather_scatter_pair(ga, slots_a, sb, slots_b)
         assert tuple(bad) == (0, 0)
-    tr["final_pages"] = be.read_pages(page_order[: 2 * bp * n_rounds: max(1, (2 * bp * n_rounds) // 32)])
+    used = min(span, 2 * bp * n_rounds)
+    tr["final_pages"] = be.read_pages(page_order[:used: max(1, used // 32)])
     tr["final_slots"] = be.read_slots(np.arange(0, 2 * bp, max(1, (2 * bp) // 16), dtype=np.int32))
     tr["count"] = ix.count()
     tr["dump"] = ix.dump()
