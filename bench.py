@@ -967,12 +967,14 @@ def main():
     dst = step.pool[: src.numel()]
     plain_ms, _ = time_calls(torch, lambda: dst.copy_(src), 5)
     out["roofline"]["plain_d2d_copy_GBps"] = 2 * src.numel() / (plain_ms * 1e-3) / 1e9
+    del src, dst
     if args.calibrate:
         cal = step.staging.view(torch.int64)
         cal.add_(1)
         torch.cuda.synchronize()
         out["calibration"] = {"kernel": "torch elementwise add_ (int64)", "bytes_read": cal.numel() * 8,
                               "bytes_written": cal.numel() * 8}
+        del cal
     gpu_hash = step.host_hash
     if not args.no_per_config:
         by_cfg = {args.config: measure_config(torch, aibx, args.config, step=step)}   # reuses the step's pool

@@ -4,9 +4,10 @@
 //
 // Layout of the work: one workgroup per request; the request is hashed by one wavefront or by
 // four together, depending on its length and on the shape of the batch (see launch_hash). A
-// wavefront takes a tile of 1024 consecutive tokens (64 coalesced tokens per load, 16 loads in
+// wavefront takes 1024 consecutive tokens at a time (64 coalesced tokens per load, 16 loads in
 // flight), so a lane always sees the same position-in-block and folds its position constant once
-// (request starts are only 4-byte aligned, so wider loads would need peeling). The per-block sums
+// (request starts are only 4-byte aligned, so wider loads would need peeling); as many such
+// sub-steps as give 64 blocks make a tile. The per-block sums
 // are formed by a transposing butterfly across the lanes that share a block (DPP lane patterns
 // inside a row of 16 lanes, bpermute only across rows), the block digests are scanned with the
 // chain's affine step (s -> K2*s + d) by DPP row shifts inside each row and a 4-step scalar chain
@@ -22,8 +23,6 @@ constexpr u64 K2 = 0xBB67AE8584CAA73Bull;
 constexpr u64 K3 = 0x3C6EF372FE94F82Bull;
 
 constexpr int kGeneralWaves = 4;  // wavefronts per request on the general path
-constexpr int kTileTokens = 1024;  // tokens per wavefront tile
-constexpr int kLoads = kTileTokens / kWave;
 
 __host__ __device__ constexpr u64 ipow(u64 base, u64 e) {
   u64 r = 1;
@@ -133,15 +132,28 @@ struct MatchOut {
   int32_t* match_len;
 };
 
-template <int kB, int kHashWaves, bool kMatch, bool kLengths>
+constexpr int kSubTokens = 1024;  // tokens a wavefront loads at a time: 16 loads of 64 tokens
+constexpr int kLoads = kSubTokens / kWave;
+
+// A tile is kSub sub-steps of 1024 tokens. Each sub-step reduces its tokens to block sums (one per
+// lane, 1024 / kB of them); the finalisers, the chain scan and the lookup run once per tile over
+// the block sums of all its sub-steps, so with kSub = kB / 16 they always work on 64 blocks and
+// their cost per token does not grow with the block size (they are 40 % of a sub-step's arithmetic:
+// 64-token blocks hashed with one sub-step per tile spend 1.9 times as long per block as with four).
+// kSub = 1 keeps a tile at 1024 tokens, which is what the lengths-only form wants: a miss is seen
+// after 1024 tokens and everything behind it is dropped.
+template <int kB, int kSub, int kHashWaves, bool kMatch, bool kLengths>
 // (7 wavefronts per SIMD: the register budget this sets - 72 instead of 95 with the lookups - costs
-// no spills and is worth 2-7 % on the fused kernel)
+// nothing in the loops and is worth 2-7 % on the fused kernel)
 __global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_eu(7, 7))) void block_hash_pow2_kernel(
     const int32_t* __restrict__ tokens, const int64_t* __restrict__ tok_off,
     const int64_t* __restrict__ blk_off, int n_req, int lg_run, u64 seed, u64* __restrict__ hash_out,
     MatchOut mo, int solo_tiles) {
   static_assert(kB == 16 || kB == 32 || kB == 64, "block size");
-  constexpr int kNB = kTileTokens / kB;   // blocks per tile
+  constexpr int kTileTokens = kSub * kSubTokens;
+  constexpr int kNBs = kSubTokens / kB;   // blocks per sub-step
+  constexpr int kNB = kSub * kNBs;        // blocks per tile
+  static_assert(kNB <= kWave && kNB >= 16, "a tile's blocks fit one wavefront");
   constexpr int kGroups = kWave / kB;     // blocks covered by one 64-token load
   constexpr int kLgB = kB == 16 ? 4 : (kB == 32 ? 5 : 6);
   __shared__ u64 lds_aggr[2][kHashWaves];
@@ -152,11 +164,14 @@ __global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_
   const int wave = threadIdx.x / kWave;
   const u64 pos_const = K0 * (u64)((lane & (kB - 1)) + 1);
   // K2^(pos+1), pos = lane within its row of 16: weight of the state entering the row
-  constexpr int kRows = kNB >= 16 ? kNB / 16 : 1;
+  constexpr int kRows = kNB / 16;
   const int row = lane >> 4;
   const u64 row_w = kChainPowers.v[lane & 15];
-  // lane that holds block `lane`'s sum after the butterfly
-  const int src_lane = ((lane % kGroups) * kB + ((lane / kGroups) << (kLgB - 4))) & (kWave - 1);
+  // This lane ends up with block `lane` of the tile, i.e. block lane % kNBs of sub-step lane / kNBs;
+  // src_lane is the lane that holds that block's sum after the sub-step's butterfly.
+  const int sub_of_lane = lane / kNBs;
+  const int blk_in_sub = lane % kNBs;
+  const int src_lane = ((blk_in_sub % kGroups) * kB + ((blk_in_sub / kGroups) << (kLgB - 4))) & (kWave - 1);
 
   // One request per workgroup. A request of at most solo_tiles tiles is hashed by wavefront 0 on
   // its own (carry in registers, no barrier; the other wavefronts leave at once); a longer one is
@@ -177,12 +192,7 @@ __global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_
   }
   int parity = 0;
   int64_t first_miss = n_r;
-  constexpr int kPack = kWave / kNB < 1 ? 1 : kWave / kNB;  // tiles per lookup round (lookups in this kernel)
-  u64 pend_h = 0;
-  int64_t pend_jb = 0;
-  bool pend_valid = false;
   bool miss_seen = false;  // wavefront-uniform: one of this wavefront's lookups has missed
-  constexpr bool lengths_only = kLengths;
   if constexpr (kLengths) {
     if (!solo && threadIdx.x < 2) lds_stop[threadIdx.x] = 0;  // ordered before its first reader by the first round's barrier
   }
@@ -195,67 +205,86 @@ __global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_
     if (!solo) parity ^= 1;
     const int64_t tile = solo ? tile0 : tile0 + wave;
     const int64_t tbase = tile * kTileTokens;
-    u64 p[kLoads];
-    // 16 coalesced loads; tokens past the last full block read as 0 and are never used
-    int32_t raw[kLoads];
-    if (tbase + kTileTokens <= n_tok) {  // whole tile inside the request: no per-load bounds checks
+    u64 csum = 0;  // sum of block `lane` of this tile
 #pragma unroll
-      for (int k = 0; k < kLoads; ++k) raw[k] = __builtin_nontemporal_load(tok + tbase + k * kWave + lane);
-    } else {
+    for (int sub = 0; sub < kSub; ++sub) {
+      const int64_t sbase = tbase + (int64_t)sub * kSubTokens;
+      if (sbase >= n_tok) break;  // nothing of the request is left (also a wavefront past the last tile)
+      u64 p[kLoads];
+      // 16 coalesced loads; tokens past the last full block read as 0 and are never used
+      int32_t raw[kLoads];
+      if (sbase + kSubTokens <= n_tok) {  // whole sub-step inside the request: no per-load bounds checks
 #pragma unroll
-      for (int k = 0; k < kLoads; ++k) {
-        const int64_t idx = tbase + k * kWave + lane;
-        raw[k] = (tile < n_tiles && idx < n_tok) ? __builtin_nontemporal_load(tok + idx) : 0;
+        for (int k = 0; k < kLoads; ++k) raw[k] = __builtin_nontemporal_load(tok + sbase + k * kWave + lane);
+#pragma unroll
+        for (int k = 0; k < kLoads; ++k) {
+          const u64 y = ((u64)(u32)raw[k] ^ pos_const) * K1;
+          p[k] = y ^ (y >> 32);
+        }
+      } else {
+#pragma unroll
+        for (int k = 0; k < kLoads; ++k) {
+          const int64_t idx = sbase + k * kWave + lane;
+          raw[k] = idx < n_tok ? __builtin_nontemporal_load(tok + idx) : 0;
+        }
+        // loads that lie behind the request's last full block altogether skip their arithmetic
+        const int live = (int)((n_tok - sbase + kWave - 1) / kWave);
+#pragma unroll
+        for (int k = 0; k < kLoads; ++k) {
+          p[k] = 0;
+          if (k < live) {
+            const u64 y = ((u64)(u32)raw[k] ^ pos_const) * K1;
+            p[k] = y ^ (y >> 32);
+          }
+        }
       }
-    }
+      // transposing butterfly: 16 partials per lane -> 1, summed over the lanes of a block
+      u64 q8[8], q4[4], q2[2], c;
+      {
+        const bool up = lane & (kB / 2);
 #pragma unroll
-    for (int k = 0; k < kLoads; ++k) {
-      const u64 y = ((u64)(u32)raw[k] ^ pos_const) * K1;
-      p[k] = y ^ (y >> 32);
-    }
-    // transposing butterfly: 16 partials per lane -> 1, summed over the lanes of a block
-    u64 q8[8], q4[4], q2[2], c;
-    {
-      const bool up = lane & (kB / 2);
-#pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        const u64 send = up ? p[t] : p[t + 8];
-        const u64 keep = up ? p[t + 8] : p[t];
-        q8[t] = keep + partner64<kB / 2>(send);
+        for (int t = 0; t < 8; ++t) {
+          const u64 send = up ? p[t] : p[t + 8];
+          const u64 keep = up ? p[t + 8] : p[t];
+          q8[t] = keep + partner64<kB / 2>(send);
+        }
       }
-    }
-    {
-      const bool up = lane & (kB / 4);
+      {
+        const bool up = lane & (kB / 4);
 #pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const u64 send = up ? q8[t] : q8[t + 4];
-        const u64 keep = up ? q8[t + 4] : q8[t];
-        q4[t] = keep + partner64<kB / 4>(send);
+        for (int t = 0; t < 4; ++t) {
+          const u64 send = up ? q8[t] : q8[t + 4];
+          const u64 keep = up ? q8[t + 4] : q8[t];
+          q4[t] = keep + partner64<kB / 4>(send);
+        }
       }
-    }
-    {
-      const bool up = lane & (kB / 8);
+      {
+        const bool up = lane & (kB / 8);
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const u64 send = up ? q4[t] : q4[t + 2];
-        const u64 keep = up ? q4[t + 2] : q4[t];
-        q2[t] = keep + partner64<kB / 8>(send);
+        for (int t = 0; t < 2; ++t) {
+          const u64 send = up ? q4[t] : q4[t + 2];
+          const u64 keep = up ? q4[t + 2] : q4[t];
+          q2[t] = keep + partner64<kB / 8>(send);
+        }
       }
+      {
+        const bool up = lane & (kB / 16);
+        const u64 send = up ? q2[0] : q2[1];
+        const u64 keep = up ? q2[1] : q2[0];
+        c = keep + partner64<kB / 16>(send);
+      }
+      if constexpr (kB >= 64) c += partner64<2>(c);
+      if constexpr (kB >= 32) c += partner64<1>(c);
+      // now the lane with load index k = (lane >> (kLgB-4)) & 15 and group g = lane / kB holds the
+      // sum of the sub-step's block k*kGroups + g; every lane fetches the block it is to hold, and
+      // the lanes of this sub-step keep it
+      c = shfl64(c, src_lane);
+      if constexpr (kSub == 1) csum = c;
+      else csum = sub_of_lane == sub ? c : csum;
     }
-    {
-      const bool up = lane & (kB / 16);
-      const u64 send = up ? q2[0] : q2[1];
-      const u64 keep = up ? q2[1] : q2[0];
-      c = keep + partner64<kB / 16>(send);
-    }
-    if constexpr (kB >= 64) c += partner64<2>(c);
-    if constexpr (kB >= 32) c += partner64<1>(c);
-    // now the lane with load index k = (lane >> (kLgB-4)) & 15 and group g = lane / kB holds the
-    // sum of block k*kGroups + g; bring block `lane` to lane `lane`
-    c = shfl64(c, src_lane);
     const int64_t jb = tile * kNB + lane;  // block index inside the request
     const bool valid = lane < kNB && jb < n_r;
-    u64 local = valid ? fin(c) : 0ull;
+    u64 local = valid ? fin(csum) : 0ull;
     // chain, level 1: scan inside each row of 16 lanes (DPP row shifts feed 0 into the row's
     // first lanes, so no lane needs a condition)
     local += ipow(K2, 1) * dpp64<kDppRowShr + 1>(local);
@@ -297,34 +326,12 @@ __global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_
         goto tile_done;
       }
     }
-    if constexpr (kMatch && kPack == 1) {
+    if constexpr (kMatch) {
       const u64 v = lookup_one(mo.table, h, valid);
       if (valid && mo.values_out) mo.values_out[b0 + jb] = v;
       const u64 miss = __ballot(valid && v == kNoValue);
       if (miss && first_miss == n_r) first_miss = tile * kNB + (__ffsll((unsigned long long)miss) - 1);
       if constexpr (kLengths) miss_seen = miss != 0 || miss_seen;
-    }
-    if constexpr (kMatch && kPack > 1) {
-      // A tile of larger blocks fills only kNB of the 64 lanes. Its hashes are parked in lane group
-      // `slot` of a pending register, and the lookup runs once kPack tiles have filled every lane
-      // (or the request ends), so each lookup round trip carries 64 probes.
-      const int slot = (int)((tile0 / stride) % kPack);
-      const u64 moved = shfl64(h, lane & (kNB - 1));
-      const int64_t moved_jb = tile * kNB + (lane & (kNB - 1));
-      if (lane / kNB == slot) {
-        pend_h = moved;
-        pend_jb = moved_jb;
-        pend_valid = tile < n_tiles && moved_jb < n_r;
-      }
-      // (with match lengths as the only output a miss should be known as early as possible: no waiting)
-      if (slot == kPack - 1 || tile0 + stride >= n_tiles || lengths_only) {
-        const u64 v = lookup_one(mo.table, pend_h, pend_valid);
-        if (pend_valid && mo.values_out) mo.values_out[b0 + pend_jb] = v;
-        const bool missed = pend_valid && v == kNoValue;
-        if (missed && pend_jb < first_miss) first_miss = pend_jb;
-        if constexpr (kLengths) miss_seen = __ballot(missed) != 0 || miss_seen;
-        pend_valid = false;
-      }
     }
   tile_done:
     if constexpr (kLengths) {
@@ -339,13 +346,6 @@ __global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_
     }
   }
   if constexpr (kMatch) {
-    if constexpr (kPack > 1) {  // first_miss was kept per lane: smallest over the wavefront
-#pragma unroll
-      for (int m = 32; m >= 1; m >>= 1) {
-        const int64_t o = (int64_t)shfl_xor64((u64)first_miss, m);
-        first_miss = o < first_miss ? o : first_miss;
-      }
-    }
     if (solo) {
       if (lane == 0) mo.match_len[r] = (int)first_miss;
     } else {
@@ -405,8 +405,8 @@ __global__ __launch_bounds__(kGeneralWaves* kWave) void block_hash_general_kerne
 namespace aibx {
 namespace {
 
-constexpr int kSoloTiles = 8;       // tiles of 1024 tokens; hashing alone
-constexpr int kSoloTilesFused = 4;  // with the lookups in the launch a wavefront's tile takes longer, so long requests are shared earlier
+constexpr int kSoloTokens = 8192;       // hashing alone
+constexpr int kSoloTokensFused = 4096;  // with the lookups in the launch a wavefront's tile takes longer, so long requests are shared earlier
 
 template <bool kMatch, bool kLengths>
 int launch_hash(const int32_t* d_tokens, const int64_t* d_tok_off, const int64_t* d_blk_off, int32_t n_req,
@@ -416,8 +416,8 @@ int launch_hash(const int32_t* d_tokens, const int64_t* d_tok_off, const int64_t
   //    shared by the four, so that a small batch finishes in few serial tiles;
   //  - thousands of requests averaging under two tiles: one wavefront per request and nothing else
   //    (workgroups of four with three idle wavefronts cost +50 % on 100,000 one-tile requests);
-  //  - thousands of longer requests: the GPU is full anyway, so a request of up to 8 tiles (4 with the
-  //    lookups in the launch) is hashed
+  //  - thousands of longer requests: the GPU is full anyway, so a request of up to 8,192 tokens (4,096
+  //    with the lookups in the launch; at least one tile) is hashed
   //    by one wavefront of its workgroup, and only longer ones - which would otherwise run on as
   //    the batch's tail - by the four together. Measured on 4 Mi-block batches against one
   //    wavefront for every request: lognormal lengths -15 % time (-24 % with the lookups in the same
@@ -427,17 +427,21 @@ int launch_hash(const int32_t* d_tokens, const int64_t* d_tok_off, const int64_t
   // (tokens -> lengths on 4 Mi-block batches: -12 % to -45 % against rounds of four).
   constexpr int kShared = kLengths ? 2 : 4;
   const int64_t mean_tokens = n_blocks_total * (int64_t)block_size / n_req;
-  const bool single = n_req >= 4096 && mean_tokens < 2 * kTileTokens;
-  const int solo_tiles = n_req < 4096 ? 1 : (kMatch ? kSoloTilesFused : kSoloTiles);
+  const bool single = n_req >= 4096 && mean_tokens < 2 * kSubTokens;
+  // sub-steps per tile: as many as fill the 64 lanes with blocks; one when only lengths are wanted
+  const int tile_tokens = kLengths ? kSubTokens : block_size * kWave;
+  const int solo_tokens = kMatch ? kSoloTokensFused : kSoloTokens;
+  const int solo_tiles = n_req < 4096 || solo_tokens < tile_tokens ? 1 : solo_tokens / tile_tokens;
   const int lg_run = request_run_lg(n_req);
   dim3 grid(kMatch ? workgroups_for_requests(n_req, lg_run) : (unsigned)n_req);
 #define AIBX_LAUNCH_HASH(B)                                                                                 \
   if (single)                                                                                               \
-    block_hash_pow2_kernel<B, 1, kMatch, kLengths><<<grid, kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off, n_req,     \
-                                                                 lg_run, seed, d_hash_out, mo, 0);          \
+    block_hash_pow2_kernel<B, (kLengths ? 1 : B / 16), 1, kMatch, kLengths><<<grid, kWave, 0, st>>>(        \
+        d_tokens, d_tok_off, d_blk_off, n_req, lg_run, seed, d_hash_out, mo, 0);                            \
   else                                                                                                      \
-    block_hash_pow2_kernel<B, kShared, kMatch, kLengths><<<grid, kShared * kWave, 0, st>>>(                          \
-        d_tokens, d_tok_off, d_blk_off, n_req, lg_run, seed, d_hash_out, mo, solo_tiles)
+    block_hash_pow2_kernel<B, (kLengths ? 1 : B / 16), kShared, kMatch, kLengths>                           \
+        <<<grid, kShared * kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off, n_req, lg_run, seed, d_hash_out, \
+                                           mo, solo_tiles)
   switch (block_size) {
     case 16: AIBX_LAUNCH_HASH(16); break;
     case 32: AIBX_LAUNCH_HASH(32); break;
