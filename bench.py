@@ -41,7 +41,8 @@ COPY_KERNEL = {"gather": "aibx::kv_copy_xcd_kernel<true, 256>", "scatter": "aibx
 # HBM bytes per gather launch of the headline workload from two rocprofv3 --pmc runs (FETCH_SIZE, then
 # WRITE_SIZE), each scaled by what the same counter reads for a plain elementwise kernel of known
 # size (--calibrate); valid only for the kernel source they were taken on.
-MEASURED_TRAFFIC = {"kvcopy_sha1": "", "config": 3, "bytes_per_launch": None}
+MEASURED_TRAFFIC = {"kvcopy_sha1": "709437eda26f340d04e93207e1559d72b3e9e339", "config": 3,
+                    "bytes_per_launch": 42951815484}
 
 
 def _u64(t):
@@ -552,6 +553,42 @@ def measure_config(torch, aibx, cfg, step=None, with_hash_match=True):
     return out
 
 
+def copy_probe(torch, aibx, wl, spec, launches, pool_pages=None):
+    """`launches` launches (after one warm-up) of one copy at the workload's pool geometry and batch
+    size, random distinct pages (2 x n x blk_bytes of traffic per launch), then one plain elementwise
+    kernel of known traffic for scaling a profiler's byte counters. pool_pages changes the number
+    of pages per plane, i.e. the distance between the planes of a layer-major pool."""
+    from workloads import Geometry, fill_pool_torch
+    layout, op = spec.split(":")
+    assert layout in ("layer", "page") and op in ("gather", "scatter"), spec
+    g = wl.geom
+    if pool_pages is not None:
+        g = Geometry(g.n_seg, g.seg_bytes, int(pool_pages), g.layout)
+    n = min(wl.batch_pages, g.n_pages // 2)
+    pool = torch.empty(g.pool_bytes, dtype=torch.uint8, device="cuda")
+    fill_pool_torch(pool, wl.kv_dtype, wl.cfg)
+    staging = torch.empty(n * g.blk_bytes, dtype=torch.uint8, device="cuda")
+    staging.view(torch.int64).random_()
+    if layout == "layer":
+        desc = aibx.make_pool_desc(pool, *g.as_tuple())
+    else:
+        desc = aibx.make_pool_desc(pool, 1, g.blk_bytes * g.n_pages, g.blk_bytes, g.blk_bytes, g.n_pages)
+    perm = np.random.default_rng(wl.cfg).permutation(g.n_pages).astype(np.int32)
+    pages = torch.from_numpy(perm[:n].copy()).cuda()
+    fn = aibx.aibx_kv_gather if op == "gather" else aibx.aibx_kv_scatter
+    ms, best = time_calls(torch, lambda: fn(desc, pages, None, n, staging, g.blk_bytes), launches, warm=1)
+    cal = staging.view(torch.int64)          # known traffic for scaling the profiler's byte counters
+    cal.add_(1)
+    torch.cuda.synchronize()
+    traffic = 2 * n * g.blk_bytes
+    return {"probe": spec, "config": wl.cfg, "pool_pages": g.n_pages, "plane_stride_MiB": g.seg_stride / 2**20,
+            "n_seg": g.n_seg if layout == "layer" else 1,
+            "seg_bytes": g.seg_bytes if layout == "layer" else g.blk_bytes, "blocks": n, "launches": launches + 1,
+            "bytes_per_launch": traffic, "median_ms": ms, "GBps": traffic / ms / 1e6,
+            "calibration": {"kernel": "torch elementwise add_ (int64)", "bytes_read": cal.numel() * 8,
+                            "bytes_written": cal.numel() * 8}}
+
+
 # ---- the oracle on the host ------------------------------------------------------------------------
 def _host_info():
     model = "unknown"
@@ -903,6 +940,15 @@ def main():
                     help="leave out the per_config array (the other four workloads are then not run)")
     ap.add_argument("--only-steps", action="store_true",
                     help="run the warm-up and the timed steps and nothing else (for profiler runs)")
+    ap.add_argument("--copy-probe", metavar="LAYOUT:OP", default=None,
+                    help="profiler aid: nothing but --steps launches of one copy at the workload's pool "
+                         "geometry; LAYOUT layer|page, OP gather|scatter (e.g. layer:scatter)")
+    ap.add_argument("--pool-pages", type=int, default=None,
+                    help="with --copy-probe: pages per plane of the pool (sets the plane stride) instead of "
+                         "the workload's own")
+    ap.add_argument("--hash-match-probe", metavar="F", type=float, default=None,
+                    help="profiler aid: nothing but the scaled hash+match batch with the index holding the "
+                         "first fraction F of every request's blocks")
     ap.add_argument("--survey", action="store_true",
                     help="instead of the headline line, print one JSON line per config (both pool "
                          "layouts) with copy bandwidths, call latencies and index rates")
@@ -924,6 +970,18 @@ def main():
             print(json.dumps(survey_config(torch, aibx, cfg, layout)), flush=True)
         return
     wl = make_workload(args.config, "full")
+    if args.copy_probe is not None:
+        print(json.dumps(copy_probe(torch, aibx, wl, args.copy_probe, args.steps, args.pool_pages)))
+        return
+    if args.hash_match_probe is not None:
+        from workloads import filler_keys
+        storage = torch.empty(aibx.aibx_index_storage_bytes(wl.n_slots), dtype=torch.uint8, device="cuda")
+        ix = aibx.aibx_index_create(storage, wl.n_slots)
+        fk, fv = filler_keys(args.config, max(wl.n_live_target, 1))
+        res = hash_match_at_fractions(torch, aibx, wl, ix, _dev_u64(torch, fk), _dev_u64(torch, fv),
+                                      fractions=(args.hash_match_probe,))
+        print(json.dumps(res))
+        return
     step = make_step(torch, aibx, wl)
     for _ in range(args.warmup):
         step.run()
@@ -960,6 +1018,12 @@ def main():
         "roofline": roof_g, "roofline_scatter": roof_s,
     }
     if args.only_steps:
+        if args.calibrate:
+            cal = step.staging.view(torch.int64)
+            cal.add_(1)
+            torch.cuda.synchronize()
+            out["calibration"] = {"kernel": "torch elementwise add_ (int64)", "bytes_read": cal.numel() * 8,
+                                  "bytes_written": cal.numel() * 8}
         print(json.dumps(out))
         return
     # what a library device-to-device copy of a staging-sized volume reaches on this GPU, for context

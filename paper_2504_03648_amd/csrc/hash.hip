@@ -115,6 +115,34 @@ __device__ __forceinline__ u64 partner64(u64 v) {
   else return dpp64<kDppQuadSwap>(v);
 }
 
+// One step of the transposing butterfly across lane bit kMask: of the two partials a and b, lanes
+// with the bit clear keep a and receive their partner's a, lanes with the bit set keep b and
+// receive their partner's b; the result is the sum. Across rows (16 or 32 lanes apart) this is
+// what the row-swapping instructions of this GPU do to a pair of registers - one swap per 32-bit
+// half and no selects, where the LDS crossbar (ds_bpermute) needs a select of what to send, a
+// select of what to keep and a round trip through the LDS for each half. Inside a row the DPP
+// patterns serve.
+typedef __attribute__((ext_vector_type(2))) unsigned swapped_t;
+template <int kMask>
+__device__ __forceinline__ u64 exchange_add(u64 a, u64 b, bool bit_set) {
+  if constexpr (kMask == 32 || kMask == 16) {
+    swapped_t lo, hi;
+    if constexpr (kMask == 32) {  // rows 2,3 of the first operand <-> rows 0,1 of the second
+      lo = __builtin_amdgcn_permlane32_swap((u32)a, (u32)b, false, false);
+      hi = __builtin_amdgcn_permlane32_swap((u32)(a >> 32), (u32)(b >> 32), false, false);
+    } else {                      // odd rows of the first operand <-> even rows of the second
+      lo = __builtin_amdgcn_permlane16_swap((u32)a, (u32)b, false, false);
+      hi = __builtin_amdgcn_permlane16_swap((u32)(a >> 32), (u32)(b >> 32), false, false);
+    }
+    // first result: the lane's own kept partial; second: the partner's partial of the same kind
+    return (((u64)hi.x << 32) | lo.x) + (((u64)hi.y << 32) | lo.y);
+  } else {
+    const u64 send = bit_set ? a : b;
+    const u64 keep = bit_set ? b : a;
+    return keep + partner64<kMask>(send);
+  }
+}
+
 __device__ __forceinline__ u64 readlane64(u64 v, int lane) {
   const u32 lo = (u32)__builtin_amdgcn_readlane((int)(u32)v, lane);
   const u32 hi = (u32)__builtin_amdgcn_readlane((int)(u32)(v >> 32), lane);
@@ -240,39 +268,13 @@ __global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_
       }
       // transposing butterfly: 16 partials per lane -> 1, summed over the lanes of a block
       u64 q8[8], q4[4], q2[2], c;
-      {
-        const bool up = lane & (kB / 2);
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-          const u64 send = up ? p[t] : p[t + 8];
-          const u64 keep = up ? p[t + 8] : p[t];
-          q8[t] = keep + partner64<kB / 2>(send);
-        }
-      }
-      {
-        const bool up = lane & (kB / 4);
+      for (int t = 0; t < 8; ++t) q8[t] = exchange_add<kB / 2>(p[t], p[t + 8], lane & (kB / 2));
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const u64 send = up ? q8[t] : q8[t + 4];
-          const u64 keep = up ? q8[t + 4] : q8[t];
-          q4[t] = keep + partner64<kB / 4>(send);
-        }
-      }
-      {
-        const bool up = lane & (kB / 8);
+      for (int t = 0; t < 4; ++t) q4[t] = exchange_add<kB / 4>(q8[t], q8[t + 4], lane & (kB / 4));
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const u64 send = up ? q4[t] : q4[t + 2];
-          const u64 keep = up ? q4[t + 2] : q4[t];
-          q2[t] = keep + partner64<kB / 8>(send);
-        }
-      }
-      {
-        const bool up = lane & (kB / 16);
-        const u64 send = up ? q2[0] : q2[1];
-        const u64 keep = up ? q2[1] : q2[0];
-        c = keep + partner64<kB / 16>(send);
-      }
+      for (int t = 0; t < 2; ++t) q2[t] = exchange_add<kB / 8>(q4[t], q4[t + 2], lane & (kB / 8));
+      c = exchange_add<kB / 16>(q2[0], q2[1], lane & (kB / 16));
       if constexpr (kB >= 64) c += partner64<2>(c);
       if constexpr (kB >= 32) c += partner64<1>(c);
       // now the lane with load index k = (lane >> (kLgB-4)) & 15 and group g = lane / kB holds the
