@@ -532,7 +532,7 @@ def measure_config(torch, aibx, cfg, step=None, with_hash_match=True):
     ix = aibx.aibx_index_create(storage, wl.n_slots)
     aibx.aibx_block_hash(d_tok, d_to, d_bo, R, N, B, 0, h)
     c = torch.zeros(5, dtype=torch.int64, device="cuda")
-    aibx.aibx_index_insert(ix, h, (h >> 8) & ((1 << 56) - 1), N, c[0:3])
+    aibx.aibx_index_insert(ix, h, ((h >> 8) & ((1 << 56) - 1)) | 0xFF, N, c[0:3])   # read as pod sets: all of 8 pods
     n_fill = max(0, wl.n_live_target - int(c[0].item()))
     fk, fv = filler_keys(cfg, max(wl.n_live_target, 1))
     fk, fv = _dev_u64(torch, fk), _dev_u64(torch, fv)
@@ -542,9 +542,29 @@ def measure_config(torch, aibx, cfg, step=None, with_hash_match=True):
     ms_m, _ = time_calls(torch, lambda: aibx.aibx_prefix_match(ix, h, d_bo, R, N, v, m), 20)
     ms_f, _ = time_calls(torch, lambda: aibx.aibx_hash_match(ix, d_tok, d_to, d_bo, R, N, B, 0, None, v, m), 20)
     ms_l, _ = time_calls(torch, lambda: aibx.aibx_hash_match(ix, d_tok, d_to, d_bo, R, N, B, 0, None, None, m), 20)
+    # the routing decision for the batch (8 pods, threshold 1/2): three launches, two, one
+    load = torch.zeros(8, dtype=torch.int32, device="cuda")
+    pod = torch.empty(R, dtype=torch.int32, device="cuda")
+    hit = torch.empty(R, dtype=torch.int32, device="cuda")
+
+    def three():
+        aibx.aibx_block_hash(d_tok, d_to, d_bo, R, N, B, 0, h)
+        aibx.aibx_prefix_match(ix, h, d_bo, R, N, v, m)
+        aibx.aibx_route(v, d_bo, R, N, 8, load, 1, 2, pod, hit)
+
+    def two():
+        aibx.aibx_hash_match(ix, d_tok, d_to, d_bo, R, N, B, 0, None, v, m)
+        aibx.aibx_route(v, d_bo, R, N, 8, load, 1, 2, pod, hit)
+    ms_3, _ = time_calls(torch, three, 20)
+    ms_2, _ = time_calls(torch, two, 20)
+    want = (pod.clone(), hit.clone())
+    ms_1, _ = time_calls(torch, lambda: aibx.aibx_hash_match_route(ix, d_tok, d_to, d_bo, R, N, B, 0, 8, load, 1, 2,
+                                                                   pod, hit), 20)
+    assert torch.equal(pod, want[0]) and torch.equal(hit, want[1])
     out["native"] = {"requests": R, "blocks": N, "hash_us": ms_h * 1e3, "match_us": ms_m * 1e3,
                      "hash_match_one_launch_us": ms_f * 1e3, "lengths_only_one_launch_us": ms_l * 1e3,
-                     "every_block_present": True}
+                     "tokens_to_pod_three_launches_us": ms_3 * 1e3, "tokens_to_pod_two_launches_us": ms_2 * 1e3,
+                     "tokens_to_pod_one_launch_us": ms_1 * 1e3, "every_block_present": True}
     out["random_read_calibration"] = random_read_calibration(torch, aibx, wl.n_slots)
     out["hash_match"] = hash_match_at_fractions(torch, aibx, wl, ix, fk, fv)
     aibx.aibx_index_destroy(ix)

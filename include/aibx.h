@@ -10,6 +10,7 @@
  *   aibx_prefix_match  lookup of those hashes in a GPU-resident cache index + first-miss length
  *   aibx_hash_match    the two above in one launch
  *   aibx_route         per request: the pod with the longest cached prefix, if above a threshold
+ *   aibx_hash_match_route  tokens in, pod out: the three above in one launch
  *   aibx_index_insert  metadata update: (key -> value) upsert           (Section 3.2.5)
  *   aibx_index_evict   metadata update: removal of evicted keys          (Section 3.2.5)
  *   aibx_index_touch / _age / _select_victims   scan-resistant victim selection (Section 3.2.5)
@@ -252,6 +253,20 @@ int aibx_route(const uint64_t* d_pod_sets, const int64_t* d_blk_off, int32_t n_r
                int64_t n_blocks_total, int32_t n_pods, const int32_t* d_pod_load,
                uint64_t threshold_num, uint64_t threshold_den, int32_t* d_pod_out,
                int32_t* d_hit_len_out, void* stream);
+
+/* The routing decision straight from the tokens, in one launch: aibx_block_hash, then the lookups of
+ * aibx_prefix_match, then the decision of aibx_route on the values found, with no hash, value or
+ * length array in between (what the gateway of Section 3.2.2 needs per batch of requests, where
+ * three launches cost more than the work). Results are exactly those of the three calls in a row:
+ * d_pod_out and d_hit_len_out as for aibx_route with d_pod_sets = the per-block index values.
+ * Work on a request ends at the first block that no single pod holds together with all blocks
+ * before it. Arguments as for aibx_hash_match and aibx_route.
+ * Errors: INVALID_ARG, ALIGN, UNSUPPORTED (block size outside {16, 32, 64}), HIP. */
+int aibx_hash_match_route(const aibx_index_t* index, const int32_t* d_tokens, const int64_t* d_tok_off,
+                          const int64_t* d_blk_off, int32_t n_req, int64_t n_blocks_total,
+                          int32_t block_size, uint64_t seed, int32_t n_pods, const int32_t* d_pod_load,
+                          uint64_t threshold_num, uint64_t threshold_den, int32_t* d_pod_out,
+                          int32_t* d_hit_len_out, void* stream);
 
 /* ------------------------------------------------------------------------------------------
  * Paged-KV gather / scatter.  (Moving KV blocks between the engine's paged memory and the

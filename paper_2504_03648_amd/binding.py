@@ -18,7 +18,7 @@ EXPORTS = [
     "aibx_index_clear", "aibx_index_insert", "aibx_index_evict", "aibx_index_count",
     "aibx_index_dump", "aibx_index_touch", "aibx_index_age", "aibx_index_select_victims",
     "aibx_index_stats", "aibx_index_rebuild",
-    "aibx_prefix_match", "aibx_hash_match", "aibx_route", "aibx_kv_gather", "aibx_kv_scatter", "aibx_kv_copy_launches", "aibx_kv_gather_runs", "aibx_kv_scatter_runs", "aibx_kv_offload", "aibx_kv_onload",
+    "aibx_prefix_match", "aibx_hash_match", "aibx_route", "aibx_hash_match_route", "aibx_kv_gather", "aibx_kv_scatter", "aibx_kv_copy_launches", "aibx_kv_gather_runs", "aibx_kv_scatter_runs", "aibx_kv_offload", "aibx_kv_onload",
     "aibx_calib_random_reads",
 ]
 
@@ -82,6 +82,7 @@ def load(build_if_missing: bool = True):
     lib.aibx_index_select_victims.argtypes = [vp, C.c_uint32, C.c_uint32, vp, vp, u64, vp, vp]
     lib.aibx_route.argtypes = [vp, vp, i32, i64, i32, vp, u64, u64, vp, vp, vp]
     lib.aibx_hash_match.argtypes = [vp, vp, vp, vp, i32, i64, i32, u64, vp, vp, vp, vp]
+    lib.aibx_hash_match_route.argtypes = [vp, vp, vp, vp, i32, i64, i32, u64, i32, vp, u64, u64, vp, vp, vp]
     for f in (lib.aibx_kv_gather, lib.aibx_kv_scatter):
         f.argtypes = [C.POINTER(PoolDesc), vp, vp, i64, vp, u64, vp, vp]
     lib.aibx_kv_copy_launches.argtypes = [C.POINTER(PoolDesc), i64, vp, vp, vp, i32]
@@ -226,6 +227,15 @@ def aibx_route(d_pod_sets, d_blk_off, n_req, n_blocks_total, n_pods, d_pod_load,
         _p(d_pod_sets, U64), _p(d_blk_off, torch.int64), int(n_req), int(n_blocks_total), int(n_pods),
         _p(d_pod_load, torch.int32), int(threshold_num), int(threshold_den),
         _p(d_pod_out, torch.int32), _p(d_hit_len_out, torch.int32), _s(stream)))
+
+
+def aibx_hash_match_route(index, d_tokens, d_tok_off, d_blk_off, n_req, n_blocks_total, block_size, seed, n_pods,
+                          d_pod_load, threshold_num, threshold_den, d_pod_out, d_hit_len_out, stream=None):
+    _check("aibx_hash_match_route", load().aibx_hash_match_route(
+        index, _p(d_tokens, torch.int32), _p(d_tok_off, torch.int64), _p(d_blk_off, torch.int64), int(n_req),
+        int(n_blocks_total), int(block_size), int(seed) & 0xFFFFFFFFFFFFFFFF, int(n_pods),
+        _p(d_pod_load, torch.int32), int(threshold_num), int(threshold_den), _p(d_pod_out, torch.int32),
+        _p(d_hit_len_out, torch.int32), _s(stream)))
 
 
 def make_pool_desc(d_pool, n_seg, seg_stride, page_stride, seg_bytes, n_pages) -> PoolDesc:

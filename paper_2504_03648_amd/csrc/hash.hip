@@ -158,6 +158,12 @@ struct MatchOut {
   Table table;
   u64* values_out;      // nullable
   int32_t* match_len;
+  // routing decision in the same launch (kRoute): index values are read as pod sets
+  int n_pods;
+  const int32_t* pod_load;
+  u64 thr_num, thr_den;
+  int32_t* pod_out;
+  int32_t* hit_len_out;
 };
 
 constexpr int kSubTokens = 1024;  // tokens a wavefront loads at a time: 16 loads of 64 tokens
@@ -170,7 +176,14 @@ constexpr int kLoads = kSubTokens / kWave;
 // 64-token blocks hashed with one sub-step per tile spend 1.9 times as long per block as with four).
 // kSub = 1 keeps a tile at 1024 tokens, which is what the lengths-only form wants: a miss is seen
 // after 1024 tokens and everything behind it is dropped.
-template <int kB, int kSub, int kHashWaves, bool kMatch, bool kLengths>
+//
+// kRoute (with kMatch and kLengths) turns the launch into the whole routing decision: a block's
+// index value is the set of pods holding it, the pods holding ALL of blocks 0..j are the running
+// AND of those sets, and the request is done where that AND becomes empty - the longest prefix any
+// pod holds and its holders fall out of a cross-lane AND scan per tile (carried between the
+// wavefronts of a shared request through LDS, like the chain state), then the last wavefront left
+// picks the least-loaded candidate. Tokens go in, a pod comes out; no hash or value array exists.
+template <int kB, int kSub, int kHashWaves, bool kMatch, bool kLengths, bool kRoute = false>
 // (7 wavefronts per SIMD: the register budget this sets - 72 instead of 95 with the lookups - costs
 // nothing in the loops and is worth 2-7 % on the fused kernel)
 __global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_eu(7, 7))) void block_hash_pow2_kernel(
@@ -187,6 +200,11 @@ __global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_
   __shared__ u64 lds_aggr[2][kHashWaves];
   __shared__ int lds_first[kHashWaves];
   __shared__ int lds_stop[2];  // a wavefront of the workgroup missed in the round of this parity
+  __shared__ u64 lds_set[2][kHashWaves];        // kRoute: AND of a tile's pod sets
+  __shared__ u64 lds_last_set[kHashWaves];      // kRoute: per wavefront, the last non-empty running AND ...
+  __shared__ int64_t lds_last_pos[kHashWaves];  // ... the block it belongs to ...
+  __shared__ int lds_count[kHashWaves][2];      // ... and how many of its blocks had a non-empty AND / held the fallback pod
+  static_assert(!kRoute || (kMatch && kLengths), "the routing form stops at the first empty set");
 
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
@@ -214,14 +232,40 @@ __global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_
   const int64_t n_tiles = (n_r + kNB - 1) / kNB;
   const bool solo = kHashWaves == 1 || n_tiles <= solo_tiles;
   if (solo && wave != 0) return;
+  // kRoute: one lane per pod. The least-request pod over all pods (the fallback), ties to the lower
+  // id, is the minimum of (load, id).
+  u64 my_rank = ~0ull, all_pods = 0;
+  int fallback_pod = 0;
+  if constexpr (kRoute) {
+    all_pods = (1ull << mo.n_pods) - 1ull;  // n_pods <= 63
+    if (lane < mo.n_pods) my_rank = ((u64)(u32)mo.pod_load[lane] << 8) | (u64)lane;
+    u64 best_rank = my_rank;
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+      const u64 o = shfl_xor64(best_rank, m);
+      best_rank = o < best_rank ? o : best_rank;
+    }
+    fallback_pod = (int)(best_rank & 0xFF);
+  }
   if (n_r <= 0) {
-    if (kMatch && lane == 0) mo.match_len[r] = 0;
+    if constexpr (kRoute) {
+      if (lane == 0) {
+        mo.pod_out[r] = fallback_pod;
+        mo.hit_len_out[r] = 0;
+      }
+    } else if (kMatch && lane == 0) {
+      mo.match_len[r] = 0;
+    }
     return;
   }
+  u64 alive = all_pods;   // kRoute: pods holding every block before this round's tiles
+  u64 last_set = 0;       // the last non-empty running AND this wavefront saw, and its block
+  int64_t last_pos = -1;
+  int n_nonempty = 0, n_fallback = 0;
   int parity = 0;
   int64_t first_miss = n_r;
   bool miss_seen = false;  // wavefront-uniform: one of this wavefront's lookups has missed
-  if constexpr (kLengths) {
+  if constexpr (kLengths && !kRoute) {
     if (!solo && threadIdx.x < 2) lds_stop[threadIdx.x] = 0;  // ordered before its first reader by the first round's barrier
   }
   const int64_t n_tok = n_r * kB;  // tokens that belong to full blocks
@@ -306,7 +350,7 @@ __global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_
       __syncthreads();
       // match lengths as the only output: once some wavefront has missed in the previous round,
       // every tile from here on lies behind that miss and the whole workgroup is done
-      if constexpr (kLengths) {
+      if constexpr (kLengths && !kRoute) {
         if (lds_stop[parity ^ 1]) break;
       }
       for (int w = 0; w < wave; ++w) cin = ipow(K2, kNB) * cin + lds_aggr[parity][w];
@@ -322,13 +366,43 @@ __global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_
     // wavefront's first miss can change an output any more (its tiles come in rising order): a
     // wavefront that hashes its request alone is done with it, one that shares it stops looking up
     // and tells the others (see lds_stop).
-    if constexpr (kLengths) {
+    if constexpr (kRoute) {
+      u64 v = lookup_one(mo.table, h, valid);
+      v = valid ? (v == kNoValue ? 0ull : (v & all_pods)) : all_pods;  // lanes past the end do not shrink the set
+#pragma unroll
+      for (int o = 1; o < kWave; o <<= 1) {  // inclusive AND scan over the tile's blocks
+        const u64 up = shfl_up64(v, o);
+        if (lane >= o) v &= up;
+      }
+      const u64 tile_set = readlane64(v, kWave - 1);
+      u64 before = alive;  // pods holding every block before this wavefront's tile
+      if (!solo) {
+        if (lane == 0) lds_set[parity][wave] = tile_set;
+        __syncthreads();
+        for (int w = 0; w < wave; ++w) before &= lds_set[parity][w];
+      }
+      v &= before;
+      const u64 nonempty = __ballot(valid && v != 0);  // a run of ones from lane 0
+      const int cnt = __popcll(nonempty);
+      if (cnt > 0) {
+        last_pos = tile * kNB + cnt - 1;
+        last_set = readlane64(v, cnt - 1);
+      }
+      n_nonempty += cnt;
+      n_fallback += __popcll(__ballot(valid && ((v >> fallback_pod) & 1ull)));
+      if (solo) {
+        alive = before & tile_set;
+      } else {
+        for (int w = 0; w < kHashWaves; ++w) alive &= lds_set[parity][w];
+      }
+      if (alive == 0) break;  // the same for every wavefront of the workgroup: no pod holds more
+    } else if constexpr (kLengths) {
       if (miss_seen) {
         if (solo) break;
         goto tile_done;
       }
     }
-    if constexpr (kMatch) {
+    if constexpr (kMatch && !kRoute) {
       const u64 v = lookup_one(mo.table, h, valid);
       if (valid && mo.values_out) mo.values_out[b0 + jb] = v;
       const u64 miss = __ballot(valid && v == kNoValue);
@@ -336,7 +410,7 @@ __global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_
       if constexpr (kLengths) miss_seen = miss != 0 || miss_seen;
     }
   tile_done:
-    if constexpr (kLengths) {
+    if constexpr (kLengths && !kRoute) {
       if (!solo && miss_seen && lane == 0) lds_stop[parity] = 1;
     }
     if (!solo) {
@@ -346,6 +420,43 @@ __global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_
     } else {
       carry = ipow(K2, kNB) * carry + aggr;
     }
+  }
+  if constexpr (kRoute) {
+    // the longest prefix any pod holds = the blocks with a non-empty running AND (a run from block
+    // 0), its holders = the AND at the run's last block, wherever in the workgroup that block was
+    if (!solo) {
+      if (lane == 0) {
+        lds_last_set[wave] = last_set;
+        lds_last_pos[wave] = last_pos;
+        lds_count[wave][0] = n_nonempty;
+        lds_count[wave][1] = n_fallback;
+      }
+      __syncthreads();
+      if (wave != 0) return;
+      n_nonempty = n_fallback = 0;
+      for (int w = 0; w < kHashWaves; ++w) {
+        n_nonempty += lds_count[w][0];
+        n_fallback += lds_count[w][1];
+        if (lds_last_pos[w] > last_pos || w == 0) {
+          last_pos = lds_last_pos[w];
+          last_set = lds_last_set[w];
+        }
+      }
+    }
+    const int64_t best_len = n_nonempty;
+    const bool aware = best_len > 0 && (u64)best_len * mo.thr_den >= mo.thr_num * (u64)n_r;
+    u64 rank = my_rank;
+    if (aware && !((last_set >> lane) & 1ull)) rank = ~0ull;  // candidates: the holders of the longest prefix
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+      const u64 o = shfl_xor64(rank, m);
+      rank = o < rank ? o : rank;
+    }
+    if (lane == 0) {
+      mo.pod_out[r] = (int32_t)(rank & 0xFF);
+      mo.hit_len_out[r] = (int32_t)(aware ? best_len : n_fallback);
+    }
+    return;
   }
   if constexpr (kMatch) {
     if (solo) {
@@ -410,7 +521,7 @@ namespace {
 constexpr int kSoloTokens = 8192;       // hashing alone
 constexpr int kSoloTokensFused = 4096;  // with the lookups in the launch a wavefront's tile takes longer, so long requests are shared earlier
 
-template <bool kMatch, bool kLengths>
+template <bool kMatch, bool kLengths, bool kRoute = false>
 int launch_hash(const int32_t* d_tokens, const int64_t* d_tok_off, const int64_t* d_blk_off, int32_t n_req,
                 int64_t n_blocks_total, int32_t block_size, u64 seed, u64* d_hash_out, MatchOut mo, hipStream_t st) {
   // Launch shape, from what the host knows (batch size and mean request length):
@@ -424,25 +535,33 @@ int launch_hash(const int32_t* d_tokens, const int64_t* d_tok_off, const int64_t
   //    the batch's tail - by the four together. Measured on 4 Mi-block batches against one
   //    wavefront for every request: lognormal lengths -15 % time (-24 % with the lookups in the same
   //    launch), uniform 4-tile requests equal, uniform 16-tile requests of 64-token blocks -7 % (+5 %).
-  // Wavefronts that share a long request: four; two when only the match lengths are wanted, where
-  // everything a wavefront does behind the first miss is wasted and a round of two wastes less
-  // (tokens -> lengths on 4 Mi-block batches: -12 % to -45 % against rounds of four).
+  // Wavefronts that share a long request: four; two when only the match lengths (or the routing
+  // decision) are wanted from a batch of thousands of requests, where everything a wavefront does
+  // behind the first miss is wasted and a round of two wastes less (tokens -> lengths on 4 Mi-block
+  // batches whose requests miss early: -12 % to -45 % against rounds of four). A small batch leaves
+  // most of the GPU idle, so there wasted work is free and the serial chain is what counts: four
+  // wavefronts and full tiles in every form (128 requests of 16,384 tokens with every block present,
+  // tokens -> pod: 26 us with rounds of two 1024-token tiles).
   constexpr int kShared = kLengths ? 2 : 4;
+  constexpr int kSubFew = kLengths ? 1 : 0;  // 0: as many sub-steps as fill the 64 lanes
   const int64_t mean_tokens = n_blocks_total * (int64_t)block_size / n_req;
-  const bool single = n_req >= 4096 && mean_tokens < 2 * kSubTokens;
-  // sub-steps per tile: as many as fill the 64 lanes with blocks; one when only lengths are wanted
-  const int tile_tokens = kLengths ? kSubTokens : block_size * kWave;
+  const bool small_batch = n_req < 4096;
+  const bool single = !small_batch && mean_tokens < 2 * kSubTokens;
+  const int tile_tokens = (kLengths && !small_batch) ? kSubTokens : block_size * kWave;
   const int solo_tokens = kMatch ? kSoloTokensFused : kSoloTokens;
-  const int solo_tiles = n_req < 4096 || solo_tokens < tile_tokens ? 1 : solo_tokens / tile_tokens;
+  const int solo_tiles = small_batch || solo_tokens < tile_tokens ? 1 : solo_tokens / tile_tokens;
   const int lg_run = request_run_lg(n_req);
   dim3 grid(kMatch ? workgroups_for_requests(n_req, lg_run) : (unsigned)n_req);
-#define AIBX_LAUNCH_HASH(B)                                                                                 \
-  if (single)                                                                                               \
-    block_hash_pow2_kernel<B, (kLengths ? 1 : B / 16), 1, kMatch, kLengths><<<grid, kWave, 0, st>>>(        \
-        d_tokens, d_tok_off, d_blk_off, n_req, lg_run, seed, d_hash_out, mo, 0);                            \
-  else                                                                                                      \
-    block_hash_pow2_kernel<B, (kLengths ? 1 : B / 16), kShared, kMatch, kLengths>                           \
-        <<<grid, kShared * kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off, n_req, lg_run, seed, d_hash_out, \
+#define AIBX_LAUNCH_HASH(B)                                                                                    \
+  if (single)                                                                                                  \
+    block_hash_pow2_kernel<B, (kSubFew ? kSubFew : B / 16), 1, kMatch, kLengths, kRoute><<<grid, kWave, 0, st>>>( \
+        d_tokens, d_tok_off, d_blk_off, n_req, lg_run, seed, d_hash_out, mo, 0);                               \
+  else if (small_batch)                                                                                        \
+    block_hash_pow2_kernel<B, B / 16, 4, kMatch, kLengths, kRoute><<<grid, 4 * kWave, 0, st>>>(                \
+        d_tokens, d_tok_off, d_blk_off, n_req, lg_run, seed, d_hash_out, mo, solo_tiles);                      \
+  else                                                                                                         \
+    block_hash_pow2_kernel<B, (kSubFew ? kSubFew : B / 16), kShared, kMatch, kLengths, kRoute>                 \
+        <<<grid, kShared * kWave, 0, st>>>(d_tokens, d_tok_off, d_blk_off, n_req, lg_run, seed, d_hash_out,    \
                                            mo, solo_tiles)
   switch (block_size) {
     case 16: AIBX_LAUNCH_HASH(16); break;
@@ -496,7 +615,7 @@ extern "C" int aibx_hash_match(const aibx_index_t* index, const int32_t* d_token
     return aibx_prefix_match(index, d_hash_out, d_blk_off, n_req, n_blocks_total, d_values_out, d_match_len,
                              stream);
   }
-  MatchOut mo;
+  MatchOut mo = {};
   mo.table = table_of(index);
   mo.values_out = d_values_out;
   mo.match_len = d_match_len;
@@ -505,4 +624,33 @@ extern "C" int aibx_hash_match(const aibx_index_t* index, const int32_t* d_token
                                    mo, as_stream(stream));
   return launch_hash<true, false>(d_tokens, d_tok_off, d_blk_off, n_req, n_blocks_total, block_size, seed, d_hash_out,
                                   mo, as_stream(stream));
+}
+
+extern "C" int aibx_hash_match_route(const aibx_index_t* index, const int32_t* d_tokens, const int64_t* d_tok_off,
+                                     const int64_t* d_blk_off, int32_t n_req, int64_t n_blocks_total,
+                                     int32_t block_size, uint64_t seed, int32_t n_pods, const int32_t* d_pod_load,
+                                     uint64_t threshold_num, uint64_t threshold_den, int32_t* d_pod_out,
+                                     int32_t* d_hit_len_out, void* stream) {
+  using namespace aibx;
+  if (!index || n_req < 0 || n_blocks_total < 0 || block_size < 1 || block_size > 1024) return AIBX_ERR_INVALID_ARG;
+  if (n_pods < 1 || n_pods > 63 || threshold_den == 0) return AIBX_ERR_INVALID_ARG;
+  if (threshold_num > 0xFFFFFFFFull || threshold_den > 0xFFFFFFFFull) return AIBX_ERR_INVALID_ARG;
+  if (n_req == 0) return AIBX_OK;
+  if (!d_tok_off || !d_blk_off || !d_pod_load || !d_pod_out || !d_hit_len_out) return AIBX_ERR_INVALID_ARG;
+  if (n_blocks_total > 0 && !d_tokens) return AIBX_ERR_INVALID_ARG;
+  if (!aligned(d_tokens, 4) || !aligned(d_tok_off, 8) || !aligned(d_blk_off, 8) || !aligned(d_pod_load, 4) ||
+      !aligned(d_pod_out, 4) || !aligned(d_hit_len_out, 4))
+    return AIBX_ERR_ALIGN;
+  // other block sizes would need a hash array to hand over between launches, which this call has not
+  if (block_size != 16 && block_size != 32 && block_size != 64) return AIBX_ERR_UNSUPPORTED;
+  MatchOut mo = {};
+  mo.table = table_of(index);
+  mo.n_pods = n_pods;
+  mo.pod_load = d_pod_load;
+  mo.thr_num = threshold_num;
+  mo.thr_den = threshold_den;
+  mo.pod_out = d_pod_out;
+  mo.hit_len_out = d_hit_len_out;
+  return launch_hash<true, true, true>(d_tokens, d_tok_off, d_blk_off, n_req, n_blocks_total, block_size, seed, nullptr,
+                                       mo, as_stream(stream));
 }

@@ -73,6 +73,17 @@ def test_argument_errors_are_raised_before_any_launch(lib):
     assert lib.aibx_index_rebuild(None, None, None, None) == -1
     assert lib.aibx_index_select_victims(None, 2, 5, fake, fake, 1, fake, None) == -1
     assert lib.aibx_hash_match(None, fake, fake, fake, 1, 1, 16, 0, fake, fake, fake, None) == -1
+    # routing straight from the tokens
+    f = lib.aibx_hash_match_route
+    h1 = C.c_void_p(0x2000)   # stands for an index handle; never dereferenced before the checks below fail
+    assert f(None, fake, fake, fake, 1, 1, 16, 0, 8, fake, 1, 2, fake, fake, None) == -1
+    assert f(h1, fake, fake, fake, 1, 1, 16, 0, 0, fake, 1, 2, fake, fake, None) == -1
+    assert f(h1, fake, fake, fake, 1, 1, 16, 0, 64, fake, 1, 2, fake, fake, None) == -1
+    assert f(h1, fake, fake, fake, 1, 1, 16, 0, 8, fake, 1, 0, fake, fake, None) == -1
+    assert f(h1, fake, fake, fake, 1, 1, 16, 0, 8, None, 1, 2, fake, fake, None) == -1
+    assert f(h1, fake, odd, fake, 1, 1, 16, 0, 8, fake, 1, 2, fake, fake, None) == -2
+    assert f(h1, fake, fake, fake, 1, 1, 24, 0, 8, fake, 1, 2, fake, fake, None) == -3
+    assert f(h1, fake, fake, fake, 0, 0, 16, 0, 8, fake, 1, 2, fake, fake, None) == 0
     # routing
     assert lib.aibx_route(fake, fake, 1, 1, 0, fake, 1, 2, fake, fake, None) == -1
     assert lib.aibx_route(fake, fake, 1, 1, 64, fake, 1, 2, fake, fake, None) == -1

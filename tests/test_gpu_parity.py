@@ -580,6 +580,62 @@ def test_route_parity(n_pods, num, den):
     assert want_hit.max() > 64
 
 
+@pytest.mark.parametrize("B,n_req,n_pods,num,den", [(16, 70, 7, 1, 2), (32, 41, 63, 1, 3), (64, 33, 5, 0, 1),
+                                                     (16, 4500, 8, 1, 2), (64, 4200, 3, 9, 10), (16, 9, 1, 2, 1)])
+def test_hash_match_route_equals_the_three_calls(B, n_req, n_pods, num, den):
+    """Tokens in, pod out: the one-launch routing decision against the oracle's hash -> match ->
+    route chain, on requests that share prefixes, with pods holding prefixes of every length
+    (none, part of a tile, whole tiles, everything), zero-block requests, and both launch shapes
+    (small batches share long requests between wavefronts; thousands of requests get one each)."""
+    import torch
+    import paper_2504_03648_amd as aibx
+    rng = np.random.default_rng(B * 1000 + n_req)
+    big = n_req >= 4096
+    tok, tok_off, lens = _ragged(rng, n_req, 0, 700 if big else 6000)
+    lens[:5] = [0, B - 1, B, 64 * B, 64 * B + 1][: min(5, n_req)]
+    tok_off = np.zeros(n_req + 1, dtype=np.int64)
+    np.cumsum(lens, out=tok_off[1:])
+    tok = rng.integers(0, 32000, size=int(tok_off[-1]), dtype=np.int32)
+    for r in range(1, n_req, 3):                                       # every third request repeats its neighbour's start
+        k = int(min(lens[r], lens[r - 1]) * rng.random())
+        tok[tok_off[r]:tok_off[r] + k] = tok[tok_off[r - 1]:tok_off[r - 1] + k]
+    blk_off = np.zeros(n_req + 1, dtype=np.int64)
+    np.cumsum(lens // B, out=blk_off[1:])
+    h = oracle.block_hash(tok, tok_off, blk_off, B, 11)
+    n = len(h)
+    sets = np.zeros(n, dtype=np.uint64)                                # which pods hold block b of which request
+    for r in range(n_req):
+        n_r = int(blk_off[r + 1] - blk_off[r])
+        for p in rng.integers(0, n_pods, size=3):
+            L = int(rng.choice([0, n_r, rng.integers(0, n_r + 1), min(n_r, 64), min(n_r, 65)]))
+            sets[blk_off[r]:blk_off[r] + L] |= np.uint64(1) << np.uint64(p)
+    uniq, inv = np.unique(h, return_inverse=True)
+    per_key = np.zeros(len(uniq), dtype=np.uint64)
+    np.bitwise_or.at(per_key, inv, sets)                               # a shared block is held by the union
+    present = per_key != 0
+    gi, oi = HipIndex(1 << 18), oracle.Index(1 << 18)
+    for ix in (gi, oi):
+        ix.insert(uniq[present], per_key[present])
+        ix.insert(rng.integers(1, 2**63, size=50000, dtype=np.uint64), np.full(50000, 1, dtype=np.uint64))
+    load = rng.integers(0, 4, size=n_pods).astype(np.int32)
+    values, _ = oi.match(h, blk_off)
+    want_pod, want_hit = oracle.route(values, blk_off, n_pods, load, num, den)
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    pod = torch.full((n_req,), -9, dtype=torch.int32, device="cuda")
+    hit = torch.full((n_req,), -9, dtype=torch.int32, device="cuda")
+    aibx.aibx_hash_match_route(gi.h, d(tok), d(tok_off), d(blk_off), n_req, n, B, 11, n_pods, d(load), num, den, pod, hit)
+    assert np.array_equal(pod.cpu().numpy(), want_pod) and np.array_equal(hit.cpu().numpy(), want_hit)
+    assert want_hit.max() > (64 if not big else 8) and (want_hit == 0).any()
+    # and the three library calls in a row agree as well
+    hh = torch.empty(n, dtype=torch.int64, device="cuda")
+    vv = torch.empty(n, dtype=torch.int64, device="cuda")
+    mm = torch.empty(n_req, dtype=torch.int32, device="cuda")
+    pod3, hit3 = torch.empty_like(pod), torch.empty_like(hit)
+    aibx.aibx_hash_match(gi.h, d(tok), d(tok_off), d(blk_off), n_req, n, B, 11, hh, vv, mm)
+    aibx.aibx_route(vv, d(blk_off), n_req, n, n_pods, d(load), num, den, pod3, hit3)
+    assert torch.equal(pod, pod3) and torch.equal(hit, hit3)
+
+
 # ---- gather / scatter --------------------------------------------------------------------------
 @pytest.mark.parametrize("n_seg,seg_bytes,n_pages,n", [
     (1, 262144, 40, 23), (64, 32768, 24, 17), (61, 73728, 12, 9), (5, 16, 50, 33),
