@@ -81,6 +81,9 @@ def _load():
         for f in (lib.orc_kv_gather, lib.orc_kv_scatter):
             f.argtypes = [C.POINTER(_PoolDesc), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
                           C.c_uint64, C.c_void_p]
+        for f in (lib.orc_kv_gather_fill, lib.orc_kv_scatter_fill):
+            f.argtypes = [C.POINTER(_PoolDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
+                          C.c_uint64, C.c_void_p]
         for f in (lib.orc_kv_gather_runs, lib.orc_kv_scatter_runs):
             f.argtypes = [C.POINTER(_PoolRunsDesc), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
                           C.c_uint64, C.c_void_p]
@@ -253,6 +256,31 @@ def kv_gather(pool, geom, page_ids, slot_ids, staging, stride) -> int:
 def kv_scatter(pool, geom, page_ids, slot_ids, staging, stride) -> int:
     """staging -> pool (pool is written in place). Returns the bad-page count."""
     return _copy(_load().orc_kv_scatter, pool, geom, page_ids, slot_ids, staging, stride)
+
+
+def kv_gather_fill(pool, geom, page_ids, slot_ids, seg_fill, staging, stride) -> int:
+    """pool -> staging, entry i moving only the first seg_fill[i] bytes of each of its segments
+    (clamped to [0, seg_bytes], rounded down to a multiple of 16). Returns the bad-page count."""
+    return _copy_fill(_load().orc_kv_gather_fill, pool, geom, page_ids, slot_ids, seg_fill, staging, stride)
+
+
+def kv_scatter_fill(pool, geom, page_ids, slot_ids, seg_fill, staging, stride) -> int:
+    return _copy_fill(_load().orc_kv_scatter_fill, pool, geom, page_ids, slot_ids, seg_fill, staging, stride)
+
+
+def _copy_fill(fn, pool, geom, page_ids, slot_ids, seg_fill, staging, stride):
+    page_ids = _arr(page_ids, np.int32)
+    slot_ids = None if slot_ids is None else _arr(slot_ids, np.int32)
+    seg_fill = None if seg_fill is None else _arr(seg_fill, np.int32)
+    assert seg_fill is None or len(seg_fill) == len(page_ids)
+    assert staging.dtype == np.uint8 and staging.flags["C_CONTIGUOUS"]
+    d = _desc(pool, *geom)
+    bad = np.zeros(1, dtype=np.uint64)
+    rc = fn(C.byref(d), _ptr(page_ids), _ptr(slot_ids), _ptr(seg_fill), len(page_ids), _ptr(staging),
+            int(stride), _ptr(bad))
+    if rc != 0:
+        raise ValueError(f"oracle copy: invalid arguments (rc={rc})")
+    return int(bad[0])
 
 
 def _copy(fn, pool, geom, page_ids, slot_ids, staging, stride):

@@ -330,8 +330,14 @@ struct orc_pool_desc {
   int64_t n_pages;
 };
 
+// Partly filled blocks (the last block of a sequence whose length is not a multiple of the block
+// size; a conversation's KV ends wherever its last turn ended, Section 3.2.5): with seg_fill given,
+// entry i moves only the first seg_fill[i] bytes of each of its segments - the bytes of the tokens
+// the block holds, which come first in every segment - and leaves the rest of the segment alone on
+// both sides. reading: the count is clamped to [0, seg_bytes] and rounded down to a multiple of 16
+// (the unit every layout here is a multiple of); seg_fill == nullptr means whole segments.
 static int copy_pages(const orc_pool_desc* pool, const int32_t* page_id, const int32_t* slot_id,
-                      int64_t n, unsigned char* staging, u64 stride, u64* bad_page,
+                      const int32_t* seg_fill, int64_t n, unsigned char* staging, u64 stride, u64* bad_page,
                       bool to_staging) {
   if (!pool || n < 0 || pool->n_seg < 1) return -1;
   if (stride < (u64)pool->n_seg * pool->seg_bytes) return -1;
@@ -341,11 +347,17 @@ static int copy_pages(const orc_pool_desc* pool, const int32_t* page_id, const i
     const int64_t q = slot_id ? (int64_t)slot_id[i] : i;
     if (p < 0) continue;
     if (p >= pool->n_pages) { if (bad_page) ++*bad_page; continue; }
+    u64 moved = pool->seg_bytes;
+    if (seg_fill) {
+      const int64_t f = seg_fill[i];
+      moved = f <= 0 ? 0 : ((u64)f < pool->seg_bytes ? (u64)f : pool->seg_bytes);
+      moved -= moved % 16;
+    }
     for (int32_t s = 0; s < pool->n_seg; ++s) {
       unsigned char* in_pool = base + (u64)s * pool->seg_stride + (u64)p * pool->page_stride;
       unsigned char* in_stage = staging + (u64)q * stride + (u64)s * pool->seg_bytes;
-      if (to_staging) std::memcpy(in_stage, in_pool, pool->seg_bytes);
-      else            std::memcpy(in_pool, in_stage, pool->seg_bytes);
+      if (to_staging) std::memcpy(in_stage, in_pool, moved);
+      else            std::memcpy(in_pool, in_stage, moved);
     }
   }
   return 0;
@@ -353,13 +365,28 @@ static int copy_pages(const orc_pool_desc* pool, const int32_t* page_id, const i
 
 int orc_kv_gather(const orc_pool_desc* pool, const int32_t* page_id, const int32_t* slot_id,
                   int64_t n, void* staging, u64 staging_block_stride, u64* bad_page) {
-  return copy_pages(pool, page_id, slot_id, n, static_cast<unsigned char*>(staging),
+  return copy_pages(pool, page_id, slot_id, nullptr, n, static_cast<unsigned char*>(staging),
                     staging_block_stride, bad_page, true);
 }
 
 int orc_kv_scatter(const orc_pool_desc* pool, const int32_t* page_id, const int32_t* slot_id,
                    int64_t n, const void* staging, u64 staging_block_stride, u64* bad_page) {
-  return copy_pages(pool, page_id, slot_id, n,
+  return copy_pages(pool, page_id, slot_id, nullptr, n,
+                    const_cast<unsigned char*>(static_cast<const unsigned char*>(staging)),
+                    staging_block_stride, bad_page, false);
+}
+
+int orc_kv_gather_fill(const orc_pool_desc* pool, const int32_t* page_id, const int32_t* slot_id,
+                       const int32_t* seg_fill, int64_t n, void* staging, u64 staging_block_stride,
+                       u64* bad_page) {
+  return copy_pages(pool, page_id, slot_id, seg_fill, n, static_cast<unsigned char*>(staging),
+                    staging_block_stride, bad_page, true);
+}
+
+int orc_kv_scatter_fill(const orc_pool_desc* pool, const int32_t* page_id, const int32_t* slot_id,
+                        const int32_t* seg_fill, int64_t n, const void* staging, u64 staging_block_stride,
+                        u64* bad_page) {
+  return copy_pages(pool, page_id, slot_id, seg_fill, n,
                     const_cast<unsigned char*>(static_cast<const unsigned char*>(staging)),
                     staging_block_stride, bad_page, false);
 }
