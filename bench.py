@@ -36,13 +36,14 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0
 STAGED = np.uint64(1) << np.uint64(62)
 NO_VALUE = np.uint64(0xFFFFFFFFFFFFFFFF)
-COPY_KERNEL = {"gather": "aibx::kv_copy_xcd_kernel<true, 256>", "scatter": "aibx::kv_copy_xcd_kernel<false, 256>"}
+COPY_KERNEL = {"gather": "aibx::kv_copy_xcd_kernel<true, 256, false>",
+               "scatter": "aibx::kv_copy_xcd_kernel<false, 256, false>"}
 
 # HBM bytes per gather launch of the headline workload from two rocprofv3 --pmc runs (FETCH_SIZE, then
 # WRITE_SIZE), each scaled by what the same counter reads for a plain elementwise kernel of known
 # size (--calibrate); valid only for the kernel source they were taken on.
-MEASURED_TRAFFIC = {"kvcopy_sha1": "709437eda26f340d04e93207e1559d72b3e9e339", "config": 3,
-                    "bytes_per_launch": 42951815484}
+MEASURED_TRAFFIC = {"kvcopy_sha1": "f7993a4a54130c5281bdd6484a450703775ef58d", "config": 3,
+                    "bytes_per_launch": 42951818875}
 
 
 def _u64(t):

@@ -17,6 +17,7 @@
  *   aibx_index_rebuild compaction / resize of the index into a second table   (Section 3.2.5)
  *   aibx_kv_gather     paged KV pool -> contiguous staging (offload)     (Section 3.2.5)
  *   aibx_kv_scatter    contiguous staging -> paged KV pool (onload)      (Section 3.2.5)
+ *   aibx_kv_gather_fill / _scatter_fill  the same for partly filled blocks (a sequence's last block)
  *   aibx_kv_gather_runs / _scatter_runs  the same with a layout conversion (token-major pools)
  *   aibx_kv_offload / aibx_kv_onload   paged KV pool <-> pinned host memory, one kernel each way
  *
@@ -303,6 +304,23 @@ int aibx_kv_gather(const aibx_pool_desc* pool, const int32_t* d_page_ids,
 int aibx_kv_scatter(const aibx_pool_desc* pool, const int32_t* d_page_ids,
                     const int32_t* d_slot_ids, int64_t n, const void* d_staging,
                     uint64_t staging_block_stride, uint64_t* d_bad_page_counter, void* stream);
+
+/* The same copies for partly filled blocks. (The last block of a sequence whose length is not a
+ * multiple of the block size: a conversation's KV ends wherever its last turn ended, and offloading,
+ * migrating or re-loading it, Section 3.2.5, has to move that block's tokens too.) In every layout
+ * served here the tokens a block holds come first in each of its segments, so entry i moves only the
+ * first d_seg_fill[i] bytes of each segment and leaves the rest of the segment alone on both sides.
+ * The count is clamped to [0, seg_bytes] and rounded down to a multiple of 16; d_seg_fill = NULL
+ * moves whole segments (the calls above). Everything else - holes, out-of-range pages, slots,
+ * strides, errors - is as for aibx_kv_gather / aibx_kv_scatter.
+ *   d_seg_fill int32[n] (device), or NULL. */
+int aibx_kv_gather_fill(const aibx_pool_desc* pool, const int32_t* d_page_ids,
+                        const int32_t* d_slot_ids, const int32_t* d_seg_fill, int64_t n, void* d_staging,
+                        uint64_t staging_block_stride, uint64_t* d_bad_page_counter, void* stream);
+int aibx_kv_scatter_fill(const aibx_pool_desc* pool, const int32_t* d_page_ids,
+                         const int32_t* d_slot_ids, const int32_t* d_seg_fill, int64_t n,
+                         const void* d_staging, uint64_t staging_block_stride,
+                         uint64_t* d_bad_page_counter, void* stream);
 
 /* How aibx_kv_gather / aibx_kv_scatter split a call of n entries into kernel launches (host
  * arithmetic only; nothing is launched and no device is needed). One workgroup of 256 lanes moves

@@ -11,4 +11,4 @@ from .binding import (AibxError, PoolDesc, PoolRunsDesc, make_pool_runs_desc, ai
                       aibx_hash_match, aibx_route, aibx_hash_match_route,
                       make_pool_desc,
                       aibx_kv_gather, aibx_kv_scatter, aibx_kv_offload, aibx_kv_onload,
-                      aibx_kv_copy_launches, aibx_calib_random_reads)
+                      aibx_kv_copy_launches, aibx_calib_random_reads, aibx_kv_gather_fill, aibx_kv_scatter_fill)

@@ -18,7 +18,7 @@ EXPORTS = [
     "aibx_index_clear", "aibx_index_insert", "aibx_index_evict", "aibx_index_count",
     "aibx_index_dump", "aibx_index_touch", "aibx_index_age", "aibx_index_select_victims",
     "aibx_index_stats", "aibx_index_rebuild",
-    "aibx_prefix_match", "aibx_hash_match", "aibx_route", "aibx_hash_match_route", "aibx_kv_gather", "aibx_kv_scatter", "aibx_kv_copy_launches", "aibx_kv_gather_runs", "aibx_kv_scatter_runs", "aibx_kv_offload", "aibx_kv_onload",
+    "aibx_prefix_match", "aibx_hash_match", "aibx_route", "aibx_hash_match_route", "aibx_kv_gather", "aibx_kv_scatter", "aibx_kv_gather_fill", "aibx_kv_scatter_fill", "aibx_kv_copy_launches", "aibx_kv_gather_runs", "aibx_kv_scatter_runs", "aibx_kv_offload", "aibx_kv_onload",
     "aibx_calib_random_reads",
 ]
 
@@ -85,6 +85,8 @@ def load(build_if_missing: bool = True):
     lib.aibx_hash_match_route.argtypes = [vp, vp, vp, vp, i32, i64, i32, u64, i32, vp, u64, u64, vp, vp, vp]
     for f in (lib.aibx_kv_gather, lib.aibx_kv_scatter):
         f.argtypes = [C.POINTER(PoolDesc), vp, vp, i64, vp, u64, vp, vp]
+    for f in (lib.aibx_kv_gather_fill, lib.aibx_kv_scatter_fill):
+        f.argtypes = [C.POINTER(PoolDesc), vp, vp, vp, i64, vp, u64, vp, vp]
     lib.aibx_kv_copy_launches.argtypes = [C.POINTER(PoolDesc), i64, vp, vp, vp, i32]
     for f in (lib.aibx_kv_gather_runs, lib.aibx_kv_scatter_runs):
         f.argtypes = [C.POINTER(PoolRunsDesc), vp, vp, i64, vp, u64, vp, vp]
@@ -254,6 +256,20 @@ def aibx_kv_scatter(pool: PoolDesc, d_page_ids, d_slot_ids, n, d_staging, stagin
                     d_bad_page_counter=None, stream=None):
     _check("aibx_kv_scatter", load().aibx_kv_scatter(
         C.byref(pool), _p(d_page_ids, torch.int32), _p(d_slot_ids, torch.int32), int(n),
+        _p(d_staging), int(staging_block_stride), _p(d_bad_page_counter, U64), _s(stream)))
+
+
+def aibx_kv_gather_fill(pool: PoolDesc, d_page_ids, d_slot_ids, d_seg_fill, n, d_staging, staging_block_stride,
+                        d_bad_page_counter=None, stream=None):
+    _check("aibx_kv_gather_fill", load().aibx_kv_gather_fill(
+        C.byref(pool), _p(d_page_ids, torch.int32), _p(d_slot_ids, torch.int32), _p(d_seg_fill, torch.int32), int(n),
+        _p(d_staging), int(staging_block_stride), _p(d_bad_page_counter, U64), _s(stream)))
+
+
+def aibx_kv_scatter_fill(pool: PoolDesc, d_page_ids, d_slot_ids, d_seg_fill, n, d_staging, staging_block_stride,
+                         d_bad_page_counter=None, stream=None):
+    _check("aibx_kv_scatter_fill", load().aibx_kv_scatter_fill(
+        C.byref(pool), _p(d_page_ids, torch.int32), _p(d_slot_ids, torch.int32), _p(d_seg_fill, torch.int32), int(n),
         _p(d_staging), int(staging_block_stride), _p(d_bad_page_counter, U64), _s(stream)))
 
 

@@ -24,6 +24,7 @@ struct CopyArgs {
   unsigned char* pool;
   unsigned char* staging;
   u64* bad_page;             // nullable
+  const int32_t* seg_fill;   // nullable: bytes of each segment that entry i moves (partly filled blocks)
   u64 seg_stride, page_stride, seg_bytes, staging_stride;
   int64_t n, n_pages;
   int64_t first_entry;       // entries [first_entry, first_entry + n_here) belong to this launch
@@ -52,12 +53,17 @@ __device__ __forceinline__ void store_through(void* p, vec16 v) {
   asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(v));
 }
 
-template <bool kGather>
+template <bool kGather, bool kFill>
 __device__ __forceinline__ void copy_tile(const CopyArgs& a, const int32_t* __restrict__ page_ids,
                                           const int32_t* __restrict__ slot_ids, int64_t i, u32 tile_in_block,
                                           u32 threads) {
   const int64_t p = page_ids[i];
   const int64_t q = slot_ids ? (int64_t)slot_ids[i] : i;  // fetched together with the page id
+  u64 limit = a.seg_bytes;  // bytes of a segment that this entry moves
+  if constexpr (kFill) {    // clamped to the segment, rounded down to whole 16-byte vectors
+    const int64_t f = a.seg_fill[i];
+    limit = f <= 0 ? 0ull : (((u64)f < a.seg_bytes ? (u64)f : a.seg_bytes) & ~15ull);
+  }
   if (p < 0) return;  // hole
   if (p >= a.n_pages) {
     if (tile_in_block == 0 && threadIdx.x == 0 && a.bad_page) atomicAdd((unsigned long long*)a.bad_page, 1ull);
@@ -66,7 +72,7 @@ __device__ __forceinline__ void copy_tile(const CopyArgs& a, const int32_t* __re
   const u32 s = tile_in_block / a.chunks_per_seg;
   const u32 c = tile_in_block - s * a.chunks_per_seg;
   const u64 off = ((u64)c * threads + threadIdx.x) * 16;
-  if (off >= a.seg_bytes) return;  // ragged last chunk of a segment
+  if (off >= limit) return;  // ragged last chunk of a segment, or behind the tokens the block holds
   unsigned char* in_pool = a.pool + (u64)s * a.seg_stride + (u64)p * a.page_stride + off;
   unsigned char* in_stage = a.staging + (u64)q * a.staging_stride + (u64)s * a.seg_bytes + off;
   if (kGather) {
@@ -77,13 +83,13 @@ __device__ __forceinline__ void copy_tile(const CopyArgs& a, const int32_t* __re
 }
 
 // XCD x (= workgroup id mod 8) takes tiles [x*tiles_per_xcd, (x+1)*tiles_per_xcd)
-template <bool kGather, int kThreads>
+template <bool kGather, int kThreads, bool kFill = false>
 __global__ __launch_bounds__(kThreads) void kv_copy_xcd_kernel(CopyArgs a, const int32_t* __restrict__ page_ids,
                                                                const int32_t* __restrict__ slot_ids) {
   const u32 t = (blockIdx.x & 7u) * a.tiles_per_xcd + (blockIdx.x >> 3);
   if (t >= a.total_tiles) return;
   const u32 i = t / a.tiles_per_block;
-  copy_tile<kGather>(a, page_ids, slot_ids, a.first_entry + i, t - i * a.tiles_per_block, kThreads);
+  copy_tile<kGather, kFill>(a, page_ids, slot_ids, a.first_entry + i, t - i * a.tiles_per_block, kThreads);
 }
 
 constexpr u32 kCopyThreads = 256;  // 4 KiB tiles
@@ -105,7 +111,7 @@ u32 copy_grid(const CopyShape& s, int64_t n_here) { return (u32)((((u64)n_here *
 
 template <bool kGather>
 int launch_copy(const aibx_pool_desc* pool, const int32_t* d_page_ids, const int32_t* d_slot_ids,
-                int64_t n, void* d_staging, u64 stride, u64* d_bad, void* stream) {
+                const int32_t* d_seg_fill, int64_t n, void* d_staging, u64 stride, u64* d_bad, void* stream) {
   if (n < 0) return AIBX_ERR_INVALID_ARG;
   if (n == 0) return AIBX_OK;
   if (!pool || !pool->base || !d_page_ids || !d_staging) return AIBX_ERR_INVALID_ARG;
@@ -116,7 +122,8 @@ int launch_copy(const aibx_pool_desc* pool, const int32_t* d_page_ids, const int
   if (!aligned(pool->base, 16) || !aligned(d_staging, 16) || pool->seg_bytes % 16 || pool->seg_stride % 16 ||
       pool->page_stride % 16 || stride % 16)
     return AIBX_ERR_ALIGN;
-  if (!aligned(d_page_ids, 4) || !aligned(d_slot_ids, 4) || !aligned(d_bad, 8)) return AIBX_ERR_ALIGN;
+  if (!aligned(d_page_ids, 4) || !aligned(d_slot_ids, 4) || !aligned(d_seg_fill, 4) || !aligned(d_bad, 8))
+    return AIBX_ERR_ALIGN;
 
   CopyShape shape;
   if (!copy_shape(pool, shape)) return AIBX_ERR_UNSUPPORTED;
@@ -125,6 +132,7 @@ int launch_copy(const aibx_pool_desc* pool, const int32_t* d_page_ids, const int
   a.pool = static_cast<unsigned char*>(pool->base);
   a.staging = static_cast<unsigned char*>(d_staging);
   a.bad_page = d_bad;
+  a.seg_fill = d_seg_fill;
   a.seg_stride = pool->seg_stride;
   a.page_stride = pool->page_stride;
   a.seg_bytes = pool->seg_bytes;
@@ -143,7 +151,10 @@ int launch_copy(const aibx_pool_desc* pool, const int32_t* d_page_ids, const int
     a.first_entry = first;
     a.total_tiles = (u32)((u64)n_here * shape.tiles_per_block);
     a.tiles_per_xcd = grid / 8;
-    kv_copy_xcd_kernel<kGather, kCopyThreads><<<dim3(grid), kCopyThreads, 0, st>>>(a, d_page_ids, d_slot_ids);
+    if (d_seg_fill)
+      kv_copy_xcd_kernel<kGather, kCopyThreads, true><<<dim3(grid), kCopyThreads, 0, st>>>(a, d_page_ids, d_slot_ids);
+    else
+      kv_copy_xcd_kernel<kGather, kCopyThreads><<<dim3(grid), kCopyThreads, 0, st>>>(a, d_page_ids, d_slot_ids);
     const int rc = launch_status();
     if (rc != AIBX_OK) return rc;
   }
@@ -176,14 +187,28 @@ int aibx_kv_copy_launches(const aibx_pool_desc* pool, int64_t n, int64_t* first_
 int aibx_kv_gather(const aibx_pool_desc* pool, const int32_t* d_page_ids, const int32_t* d_slot_ids,
                    int64_t n, void* d_staging, uint64_t staging_block_stride,
                    uint64_t* d_bad_page_counter, void* stream) {
-  return aibx::launch_copy<true>(pool, d_page_ids, d_slot_ids, n, d_staging, staging_block_stride,
+  return aibx::launch_copy<true>(pool, d_page_ids, d_slot_ids, nullptr, n, d_staging, staging_block_stride,
                                  d_bad_page_counter, stream);
 }
 
 int aibx_kv_scatter(const aibx_pool_desc* pool, const int32_t* d_page_ids, const int32_t* d_slot_ids,
                     int64_t n, const void* d_staging, uint64_t staging_block_stride,
                     uint64_t* d_bad_page_counter, void* stream) {
-  return aibx::launch_copy<false>(pool, d_page_ids, d_slot_ids, n, const_cast<void*>(d_staging),
+  return aibx::launch_copy<false>(pool, d_page_ids, d_slot_ids, nullptr, n, const_cast<void*>(d_staging),
+                                  staging_block_stride, d_bad_page_counter, stream);
+}
+
+int aibx_kv_gather_fill(const aibx_pool_desc* pool, const int32_t* d_page_ids, const int32_t* d_slot_ids,
+                        const int32_t* d_seg_fill, int64_t n, void* d_staging, uint64_t staging_block_stride,
+                        uint64_t* d_bad_page_counter, void* stream) {
+  return aibx::launch_copy<true>(pool, d_page_ids, d_slot_ids, d_seg_fill, n, d_staging, staging_block_stride,
+                                 d_bad_page_counter, stream);
+}
+
+int aibx_kv_scatter_fill(const aibx_pool_desc* pool, const int32_t* d_page_ids, const int32_t* d_slot_ids,
+                         const int32_t* d_seg_fill, int64_t n, const void* d_staging,
+                         uint64_t staging_block_stride, uint64_t* d_bad_page_counter, void* stream) {
+  return aibx::launch_copy<false>(pool, d_page_ids, d_slot_ids, d_seg_fill, n, const_cast<void*>(d_staging),
                                   staging_block_stride, d_bad_page_counter, stream);
 }
 

@@ -98,6 +98,12 @@ def test_argument_errors_are_raised_before_any_launch(lib):
     assert lib.aibx_kv_gather(C.byref(d), fake, None, 1, fake, 4096, None, None) == -1  # stride < block
     assert lib.aibx_kv_gather(C.byref(d), fake, None, 1, fake, 8200, None, None) == -2
     assert lib.aibx_kv_scatter(C.byref(d), fake, None, 1, odd, 8192, None, None) == -2
+    for f in (lib.aibx_kv_gather_fill, lib.aibx_kv_scatter_fill):
+        assert f(C.byref(d), fake, None, fake, -1, fake, 8192, None, None) == -1
+        assert f(C.byref(d), fake, None, fake, 0, fake, 8192, None, None) == 0
+        assert f(None, fake, None, fake, 1, fake, 8192, None, None) == -1
+        assert f(C.byref(d), fake, None, C.c_void_p(0x1002), 1, fake, 8192, None, None) == -2   # fill counts are int32
+        assert f(C.byref(d), fake, None, fake, 1, fake, 4096, None, None) == -1     # stride < block
     for f in (lib.aibx_kv_offload, lib.aibx_kv_onload):
         assert f(C.byref(d), fake, -1, fake, 8192, None, None) == -1
         assert f(C.byref(d), fake, 0, fake, 8192, None, None) == 0

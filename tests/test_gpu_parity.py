@@ -671,6 +671,58 @@ def test_gather_scatter_parity(n_seg, seg_bytes, n_pages, n):
     hb.check_guards()                                                    # canaries around pool and staging intact
 
 
+@pytest.mark.parametrize("n_seg,seg_bytes,n_pages,n", [(64, 32768, 24, 17), (61, 73728, 12, 9), (1, 262144, 20, 20),
+                                                        (5, 48, 30, 33), (3, 4096 + 16, 30, 25), (2, 16, 4, 4)])
+def test_partly_filled_blocks_parity(n_seg, seg_bytes, n_pages, n):
+    """aibx_kv_gather_fill / _scatter_fill against the oracle: every fill from nothing to the whole
+    segment, counts that are negative, not multiples of 16 or larger than a segment, holes and
+    out-of-range pages; whole staging buffer and whole pool compared, canaries around both."""
+    import torch
+    import paper_2504_03648_amd as aibx
+    g = Geometry(n_seg, seg_bytes, n_pages)
+    rng = np.random.default_rng(n_seg * 31 + n)
+    host = rng.integers(0, 256, size=g.pool_bytes, dtype=np.uint8)
+    hb = HipBackend()
+    hb.pool_create(g, None, None, host_bytes=host.copy())
+    stride = g.blk_bytes + (48 if n_seg == 5 else 0)
+    n_slots = n + 2
+    hb.staging_create(n_slots, stride)
+    hb.staging.fill_(0x5A)
+    o_pool, o_st = host.copy(), np.full(n_slots * stride, 0x5A, dtype=np.uint8)
+    ids = rng.permutation(n_pages)[:n].astype(np.int32) if n <= n_pages else rng.integers(0, n_pages, size=n).astype(np.int32)
+    fill = (rng.integers(0, seg_bytes // 16 + 1, size=n) * 16).astype(np.int32)
+    fill[0] = seg_bytes
+    if n > 6:
+        fill[1], fill[2], fill[3], fill[4] = 0, -7, seg_bytes + 4096, min(seg_bytes, 16 * 3) - 5
+        ids[5] = -1
+        ids[6] = n_pages
+    slots = rng.permutation(n_slots)[:n].astype(np.int32)
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    bad = torch.zeros(1, dtype=torch.int64, device="cuda")
+    want_bad = oracle.kv_gather_fill(o_pool, g.as_tuple(), ids, slots, fill, o_st, stride)
+    aibx.aibx_kv_gather_fill(hb.desc, d(ids), d(slots), d(fill), n, hb.staging, stride, bad)
+    assert int(bad.item()) == want_bad == (1 if n > 6 else 0)
+    assert np.array_equal(hb.staging.cpu().numpy(), o_st)
+    assert np.array_equal(hb.pool.cpu().numpy(), o_pool)
+    # scatter other bytes back into (distinct) pages, partly
+    fresh = rng.integers(0, 256, size=n_slots * stride, dtype=np.uint8)
+    o_st[:] = fresh
+    hb.staging.copy_(torch.from_numpy(fresh))
+    pages = rng.permutation(n_pages)[: min(n, n_pages)].astype(np.int32)
+    k = len(pages)
+    bad.zero_()
+    assert oracle.kv_scatter_fill(o_pool, g.as_tuple(), pages, slots[:k], fill[:k], o_st, stride) == 0
+    aibx.aibx_kv_scatter_fill(hb.desc, d(pages), d(slots[:k]), d(fill[:k]), k, hb.staging, stride, bad)
+    assert int(bad.item()) == 0
+    assert np.array_equal(hb.pool.cpu().numpy(), o_pool)
+    assert np.array_equal(hb.staging.cpu().numpy(), o_st)
+    # NULL fill = the plain copy
+    aibx.aibx_kv_gather_fill(hb.desc, d(pages), d(slots[:k]), None, k, hb.staging, stride, bad)
+    oracle.kv_gather(o_pool, g.as_tuple(), pages, slots[:k], o_st, stride)
+    assert np.array_equal(hb.staging.cpu().numpy(), o_st)
+    hb.check_guards()
+
+
 def test_gather_then_scatter_is_identity_on_the_pool():
     g = Geometry(8, 32768, 300)
     hb = HipBackend()
