@@ -186,7 +186,9 @@ constexpr int kLoads = kSubTokens / kWave;
 template <int kB, int kSub, int kHashWaves, bool kMatch, bool kLengths, bool kRoute = false>
 // (7 wavefronts per SIMD: the register budget this sets - 72 instead of 95 with the lookups - costs
 // nothing in the loops and is worth 2-7 % on the fused kernel)
-__global__ __launch_bounds__(kHashWaves* kWave) __attribute__((amdgpu_waves_per_eu(7, 7))) void block_hash_pow2_kernel(
+// (the routing form carries more state across its tiles and gets the registers for it: 5 wavefronts)
+__global__ __launch_bounds__(kHashWaves* kWave)
+    __attribute__((amdgpu_waves_per_eu(kRoute ? 5 : 7, kRoute ? 5 : 7))) void block_hash_pow2_kernel(
     const int32_t* __restrict__ tokens, const int64_t* __restrict__ tok_off,
     const int64_t* __restrict__ blk_off, int n_req, int lg_run, u64 seed, u64* __restrict__ hash_out,
     MatchOut mo, int solo_tiles) {

@@ -52,6 +52,18 @@ def test_index_and_match_full_size(cfg):
     # the one-launch path on the same index state
     fh, fv, fm = hip_hash_match(gi, wl.tokens, wl.tok_off, wl.blk_off, wl.block_size, 0)
     assert np.array_equal(fh, h) and np.array_equal(fv, ov) and np.array_equal(fm, om)
+    # the routing decision straight from the tokens, values read as pod sets, at the batch's full size
+    import torch
+    import paper_2504_03648_amd as aibx
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    load = rng.integers(0, 4, size=8).astype(np.int32)
+    pod = torch.full((wl.n_req,), -9, dtype=torch.int32, device="cuda")
+    hit = torch.full((wl.n_req,), -9, dtype=torch.int32, device="cuda")
+    for num, den in ((1, 2), (0, 1)):
+        want_pod, want_hit = oracle.route(ov, wl.blk_off, 8, load, num, den)
+        aibx.aibx_hash_match_route(gi.h, d(wl.tokens), d(wl.tok_off), d(wl.blk_off), wl.n_req, wl.n_blocks,
+                                   wl.block_size, 0, 8, d(load), num, den, pod, hit)
+        assert np.array_equal(pod.cpu().numpy(), want_pod) and np.array_equal(hit.cpu().numpy(), want_hit)
     # eviction policy at the full table size: every request touches its blocks in its own epoch
     for r in range(0, wl.n_req, max(1, wl.n_req // 64)):
         blk = h[wl.blk_off[r]:wl.blk_off[r + 1]]

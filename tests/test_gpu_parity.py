@@ -888,6 +888,11 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
     pages = torch.from_numpy(np.random.default_rng(1).permutation(g.n_pages)[:n].astype(np.int32)).cuda()
     back = torch.from_numpy(np.random.default_rng(2).permutation(g.n_pages)[:n].astype(np.int32)).cuda()
     staging = torch.zeros(n * g.blk_bytes, dtype=torch.uint8, device="cuda")
+    staging2 = torch.zeros(n * g.blk_bytes, dtype=torch.uint8, device="cuda")
+    fill = torch.from_numpy((np.random.default_rng(3).integers(0, g.seg_bytes // 16 + 1, size=n) * 16).astype(np.int32)).cuda()
+    pod_load = torch.zeros(8, dtype=torch.int32, device="cuda")
+    pod = torch.zeros(R, dtype=torch.int32, device="cuda")
+    hit = torch.zeros(R, dtype=torch.int32, device="cuda")
 
     def sequence():
         aibx.aibx_index_clear(ix)
@@ -897,6 +902,8 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
         aibx.aibx_prefix_match(ix, h, d_bo, R, N, v, m)
         aibx.aibx_kv_gather(desc, pages, None, n, staging, g.blk_bytes, None)
         aibx.aibx_kv_scatter(desc, back, None, n, staging, g.blk_bytes, None)
+        aibx.aibx_kv_gather_fill(desc, pages, None, fill, n, staging2, g.blk_bytes, None)
+        aibx.aibx_hash_match_route(ix, d_tok, d_to, d_bo, R, N, wl.block_size, 0, 8, pod_load, 1, 2, pod, hit)
 
     # Requests share prefixes, so the batch repeats keys: values are a function of the key and the
     # evicted keys are distinct, which makes every output independent of the order of equal keys.
@@ -907,7 +914,7 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
     pool0 = pool.clone()
     sequence()
     torch.cuda.synchronize()
-    want = [x.clone() for x in (h, v, m, ev, staging, pool)]
+    want = [x.clone() for x in (h, v, m, ev, staging, pool, staging2, pod, hit)]
     assert int((v == -1).sum()) > 0 and int((v != -1).sum()) > 0
 
     side = torch.cuda.Stream()
@@ -918,14 +925,14 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
         with torch.cuda.graph(graph, stream=side):
             sequence()
     for replay in range(3):
-        for x in (h, v, ev, staging):
+        for x in (h, v, ev, staging, staging2, pod, hit):
             x.zero_()                                   # eager work between the replays
         m.fill_(-1)
         pool.copy_(pool0)
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
-        for got, w in zip((h, v, m, ev, staging, pool), want):
+        for got, w in zip((h, v, m, ev, staging, pool, staging2, pod, hit), want):
             assert torch.equal(got, w), replay
     aibx.aibx_index_destroy(ix)
 
