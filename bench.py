@@ -429,7 +429,7 @@ def hash_match_at_fractions(torch, aibx, wl, ix, fk, fv, fractions=(0.0, 0.5, 1.
         ms_l, _ = time_calls(torch, lambda: aibx.aibx_hash_match(ix, *args, None, None, m), 10)
         hit = float((v != -1).float().mean().item())
         matched = float(m.double().sum().item()) / N
-        real = 4 * B + 8 + 8 + 8 + 16 * hit + 8          # tokens, hash out and in, tag word, slot on a hit, value out
+        real = 4 * B + 8 + 8 + 16 + 16 * hit + 8         # tokens, hash out and in, a pair's tags, slot on a hit, value out
         two, one = N / ((ms_h + ms_m) * 1e-3), N / (ms_f * 1e-3)
         rows.append({
             "index_holds": f, "matched_fraction": matched, "lookup_hit_fraction": hit, "keys_from_batch": n_real,

@@ -7,7 +7,8 @@
 // is all a lookup reads until a tag matches (index_device.h).
 // Table: open addressing over buckets of 8 slots; a bucket is one 128-byte line holding its 8 keys
 // and then its 8 values. Key 0 = EMPTY, key 2^64-1 = TOMBSTONE. A key lives in the first bucket of
-// its probe sequence (home, home+step, home+2*step, ... mod n_buckets, step odd and key-dependent)
+// its probe sequence (home, its neighbour home^1, home+2*step, that one's neighbour, ... mod
+// n_buckets, step odd and key-dependent: pairs of neighbouring buckets visited by double hashing)
 // that had a free slot when it was inserted.
 // Invariant kept by every kernel: a probe sequence continues past a bucket only if that bucket
 // has no EMPTY slot; so a lookup stops at the first bucket that has one.
@@ -193,7 +194,7 @@ __global__ __launch_bounds__(kIndexThreads) void index_insert_kernel(Table t, So
     }
     // the probe sequence ends at a bucket with an EMPTY slot, or after every bucket was seen
     if (!any_empty && probes + 1 < t.probe_limit) {
-      b = (b + step) & t.bucket_mask;
+      b = next_bucket(t, b, step, probes);
       ++probes;
     } else if (!have_cand) {
       ++n_full;  // every slot the key may use is taken
@@ -275,7 +276,7 @@ __global__ __launch_bounds__(kIndexThreads) void index_evict_kernel(
       break;
     }
     if (any_empty || probes + 1 >= t.probe_limit) break;
-    b = (b + step) & t.bucket_mask;
+    b = next_bucket(t, b, step, probes);
   }
   if (values_out) values_out[i] = result;
   if (result != kNoValue) ++n_ev;
