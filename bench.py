@@ -43,7 +43,7 @@ COPY_KERNEL = {"gather": "aibx::kv_copy_xcd_kernel<true, 256, false>",
 # WRITE_SIZE), each scaled by what the same counter reads for a plain elementwise kernel of known
 # size (--calibrate); valid only for the kernel source they were taken on.
 MEASURED_TRAFFIC = {"kvcopy_sha1": "f7993a4a54130c5281bdd6484a450703775ef58d", "config": 3,
-                    "bytes_per_launch": 42951818875}
+                    "bytes_per_launch": 42951863323}
 
 
 def _u64(t):
@@ -970,6 +970,9 @@ def main():
     ap.add_argument("--hash-match-probe", metavar="F", type=float, default=None,
                     help="profiler aid: nothing but the scaled hash+match batch with the index holding the "
                          "first fraction F of every request's blocks")
+    ap.add_argument("--random-read-probe", metavar="MIB:BYTES", default=None,
+                    help="profiler aid: nothing but --steps launches of 16 Mi independent random reads of BYTES "
+                         "(8, 16, 64 or 128) from the start of random 128-byte lines of a table of MIB MiB")
     ap.add_argument("--survey", action="store_true",
                     help="instead of the headline line, print one JSON line per config (both pool "
                          "layouts) with copy bandwidths, call latencies and index rates")
@@ -989,6 +992,16 @@ def main():
         for cfg, layout in [(1, None), (2, None), (2, "page-major"), (3, None), (3, "page-major"), (4, None),
                             (4, "page-major"), (5, None), (5, "page-major")]:
             print(json.dumps(survey_config(torch, aibx, cfg, layout)), flush=True)
+        return
+    if args.random_read_probe is not None:
+        mib, rd = (int(x) for x in args.random_read_probe.split(":"))
+        table = torch.zeros(mib << 20, dtype=torch.uint8, device="cuda")
+        sink = torch.zeros(1, dtype=torch.int64, device="cuda")
+        n = 1 << 24
+        ms, _ = time_calls(torch, lambda: aibx.aibx_calib_random_reads(table, mib << 20, 128, rd, n, 1, sink),
+                           args.steps, warm=1)
+        print(json.dumps({"table_MiB": mib, "line_bytes": 128, "read_bytes": rd, "reads": n, "ms": ms,
+                          "Greads_per_s": n / (ms * 1e-3) / 1e9, "launches": args.steps + 1}))
         return
     wl = make_workload(args.config, "full")
     if args.copy_probe is not None:
