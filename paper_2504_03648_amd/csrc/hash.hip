@@ -267,6 +267,8 @@ __global__ __launch_bounds__(kHashWaves* kWave)
   int parity = 0;
   int64_t first_miss = n_r;
   bool miss_seen = false;  // wavefront-uniform: one of this wavefront's lookups has missed
+  [[maybe_unused]] bool ask = false;  // whether lookup_tile should still test a tile's last key first
+  if constexpr (kMatch) ask = mo.table.guess_present;
   if constexpr (kLengths && !kRoute) {
     if (!solo && threadIdx.x < 2) lds_stop[threadIdx.x] = 0;  // ordered before its first reader by the first round's barrier
   }
@@ -369,7 +371,7 @@ __global__ __launch_bounds__(kHashWaves* kWave)
     // wavefront that hashes its request alone is done with it, one that shares it stops looking up
     // and tells the others (see lds_stop).
     if constexpr (kRoute) {
-      u64 v = lookup_one(mo.table, h, valid);
+      u64 v = lookup_tile(mo.table, h, valid, ask);
       v = valid ? (v == kNoValue ? 0ull : (v & all_pods)) : all_pods;  // lanes past the end do not shrink the set
 #pragma unroll
       for (int o = 1; o < kWave; o <<= 1) {  // inclusive AND scan over the tile's blocks
@@ -405,7 +407,7 @@ __global__ __launch_bounds__(kHashWaves* kWave)
       }
     }
     if constexpr (kMatch && !kRoute) {
-      const u64 v = lookup_one(mo.table, h, valid);
+      const u64 v = lookup_tile(mo.table, h, valid, ask);
       if (valid && mo.values_out) mo.values_out[b0 + jb] = v;
       const u64 miss = __ballot(valid && v == kNoValue);
       if (miss && first_miss == n_r) first_miss = tile * kNB + (__ffsll((unsigned long long)miss) - 1);

@@ -46,11 +46,12 @@ __global__ __launch_bounds__(kWaves* kWave) void prefix_match_kernel(
   int64_t first_miss = n_r;
   int64_t base = (int64_t)wave * kWave;
   u64 k_next = base + lane < n_r ? hashes[b0 + base + lane] : kEmpty;
+  bool ask = t.guess_present;
   for (; base < n_r; base += kStride) {
     const bool valid = base + lane < n_r;
     const u64 k = k_next;
     k_next = base + kStride + lane < n_r ? hashes[b0 + base + kStride + lane] : kEmpty;
-    const u64 v = lookup_one(t, k, valid);
+    const u64 v = lookup_tile(t, k, valid, ask);
     if (valid && values_out) values_out[b0 + base + lane] = v;
     const u64 miss = __ballot(valid && v == kNoValue);
     if (miss && first_miss == n_r) first_miss = base + (__ffsll((unsigned long long)miss) - 1);

@@ -43,7 +43,15 @@ struct Table {
   u64 bucket_mask;
   u64 probe_limit;  // min(n_buckets, kMaxProbeBuckets): buckets of a probe sequence that are ever used
   int shift;  // 64 - lg(n_buckets); home = (key * kHomeMul) >> shift (0 buckets bits -> 0)
+  bool guess_present;  // lookups of a tile may go through the key words (lookup_tile)
 };
+// Tables from this many slots on let lookup_tile guess: their tags (4 MiB and more) no longer stay in
+// an XCD's L2, so a key that is present costs a line of tags besides its slot's line, and every line
+// that leaves the L2 is 128 bytes at the rate of a streaming read. Measured with every key present:
+// lookups 32 % (2^22 slots at load 0.7) and 28 % (2^24 at 0.75) faster, 15-17 % in the kernel that also
+// hashes; with every key absent 7-17 % slower in the lookups alone (the one dependent read in front)
+// and 0-4 % in the hashing kernel. Smaller tables lose 24-28 % on absent keys and gain at most 5 %.
+constexpr u64 kGuessPresentFrom = 1ull << 22;
 
 __device__ __forceinline__ u64 home_bucket(const Table& t, u64 key) {
   return t.shift >= 64 ? 0ull : (key * kHomeMul) >> t.shift;
@@ -58,7 +66,8 @@ __device__ __forceinline__ u64 home_bucket(const Table& t, u64 key) {
 // at a load factor of 0.75 an absent key costs 1.22 requests this way instead of 1.47).
 __device__ __forceinline__ u64 probe_step(u64 key) { return ((key * kHomeMul) >> 7) | 1ull; }
 // The bucket after b, where `probes` buckets of the sequence came before b (b is the first of its
-// pair when that count is even). Never called for a table of one bucket (its sequence has length 1).
+// pair when that count is even). In a table of one bucket the result is never used (its sequences have
+// length 1).
 __device__ __forceinline__ u64 next_bucket(const Table& t, u64 b, u64 step, u64 probes) {
   b ^= 1ull;
   return (probes & 1ull) ? (b + 2ull * step) & t.bucket_mask : b;
@@ -164,6 +173,65 @@ __device__ __forceinline__ int64_t find_slot(const Table& t, u64 key, bool valid
   return found;
 }
 
+// The same search through the key words themselves, without the tags: the lane reads the 8 keys of a
+// bucket (half of its 128-byte line) and, where its key is among them, the value from the same line.
+// For a key that is present in the first bucket of its sequence this is ONE line instead of a line
+// of tags plus the slot's line; for an absent key it is a line of slots where the tags would have
+// been 16 bytes that are mostly cached.
+__device__ __forceinline__ int64_t find_slot_in_keys(const Table& t, u64 key, bool valid, u64& value_out) {
+  int64_t found = -1;
+  bool open = valid && key != kEmpty && key != kTomb;
+  u64 b = home_bucket(t, key);
+  const u64 step = probe_step(key);
+  for (u64 probes = 0; open; ++probes) {
+    const u64* bucket = bucket_words(t, b);
+    u64 seen[kBucket];
+    load_bucket_keys(bucket, seen);
+    int hit = -1;
+    bool any_empty = false;
+#pragma unroll
+    for (int j = 0; j < kBucket; ++j) {
+      if (seen[j] == key) hit = j;
+      any_empty |= seen[j] == kEmpty;
+    }
+    if (hit >= 0) {
+      found = (int64_t)(b * kBucket + hit);
+      value_out = bucket[kBucket + hit];
+    }
+    open = hit < 0 && !any_empty && probes + 1 < t.probe_limit;
+    b = next_bucket(t, b, step, probes);
+  }
+  return found;
+}
+
+// Lookup of one tile: up to 64 consecutive blocks of one request, one per lane (every lane of the
+// wavefront must call). Consecutive blocks of a request are present as a prefix - a block's hash
+// covers everything before it, and caches drop a sequence from its end - so the tile's LAST block
+// says what to expect of the others: the wavefront reads the tags of that one key (one request) and,
+// where they show the key, looks all its keys up in the key words directly (one line per key that
+// is present); otherwise in the tags. Both searches return the same result for every key whatever
+// the guess; only their cost differs. `ask` is the caller's state per request: it starts as the
+// table's guess_present and goes off behind the first tile whose last block was absent (what
+// follows a miss is not expected to be present, and need not pay for the question).
+__device__ __forceinline__ u64 lookup_tile(const Table& t, u64 key, bool valid, bool& ask) {
+  u64 value = kNoValue;
+  const u64 live = __ballot(valid);
+  bool in_keys = false;
+  if (ask && live) {
+    const int last = 63 - __clzll((unsigned long long)live);
+    const u64 k = __shfl(key, last);  // the tile's last key, the same in every lane
+    if (k != kEmpty && k != kTomb) {
+      const u64 b = home_bucket(t, k);
+      const u64 tags = *tag_word(t, b);
+      in_keys = zero_bytes(tags ^ ((u64)tag_of(k) * kOnes)) != 0;
+    }
+    ask = in_keys;  // behind a tile whose last block is absent nothing is expected to be present
+  }
+  if (in_keys) (void)find_slot_in_keys(t, key, valid, value);
+  else (void)find_slot(t, key, valid, value);
+  return value;
+}
+
 // The key's value or kNoValue.
 __device__ __forceinline__ u64 lookup_one(const Table& t, u64 key, bool valid) {
   u64 value = kNoValue;
@@ -200,6 +268,7 @@ inline Table table_of(const aibx_index* ix) {
   t.bucket_mask = ix->n_buckets - 1;
   t.probe_limit = ix->n_buckets < kMaxProbeBuckets ? ix->n_buckets : kMaxProbeBuckets;
   t.shift = 64 - ix->lg_buckets;
+  t.guess_present = ix->n_slots >= kGuessPresentFrom;
   return t;
 }
 

@@ -101,13 +101,17 @@ def test_match_many_requests(top):
     assert om.max() > 64
 
 
-@pytest.mark.parametrize("n_blocks", [(1 << 17) + 777, (1 << 20) + 333, (1 << 22) + 5])
-def test_match_large_batches(n_blocks):
+@pytest.mark.parametrize("n_blocks,lg_slots", [((1 << 17) + 777, 16), ((1 << 20) + 333, 16), ((1 << 22) + 5, 16),
+                                               ((1 << 20) + 333, 22)])
+def test_match_large_batches(n_blocks, lg_slots):
     """Batches of 2^17 to 2^22 blocks over thousands of ragged requests; a table at load 0.75
-    with tombstones gives long probe sequences."""
+    with tombstones gives long probe sequences. On the table of 2^22 slots the lookups of a tile
+    whose last key is present go through the key words instead of the tags; the 3 % of absent keys
+    strewn over the batch make that guess wrong for single keys of most tiles."""
     rng = np.random.default_rng(n_blocks)
-    n_slots = 1 << 16
-    keys = np.unique(rng.integers(1, 2**63, size=80000, dtype=np.uint64))
+    n_slots = 1 << lg_slots
+    keys = np.unique(rng.integers(1, 2**63, size=n_slots + n_slots // 4, dtype=np.uint64))
+    rng.shuffle(keys)
     present = keys[: int(n_slots * 0.75)]
     gi, oi = HipIndex(n_slots), oracle.Index(n_slots)
     for ix in (gi, oi):
@@ -125,6 +129,9 @@ def test_match_large_batches(n_blocks):
     h[lead] = rng.choice(present, size=int(lead.sum()))
     h[5] = 0
     h[6] = NO                                                        # reserved keys read as absent
+    two = np.flatnonzero(sizes >= 2)[:2]                             # ... also as the last key of a request's last tile
+    h[blk_off[two[0] + 1] - 1] = 0
+    h[blk_off[two[1] + 1] - 1] = NO
     gv, gm = gi.match(h, blk_off)
     ov, om = oi.match(h, blk_off)
     assert np.array_equal(gv, ov) and np.array_equal(gm, om)
@@ -512,10 +519,13 @@ def test_scan_does_not_push_out_reused_blocks_full_flow():
 
 
 # ---- hash + match in one launch -------------------------------------------------------------------
-@pytest.mark.parametrize("B,n_req", [(16, 37), (32, 21), (64, 19), (16, 5000), (64, 4500), (24, 11)])
-def test_hash_match_equals_hash_then_match(B, n_req):
+@pytest.mark.parametrize("B,n_req,lg_slots", [(16, 37, 18), (32, 21, 18), (64, 19, 18), (16, 5000, 18), (64, 4500, 18),
+                                              (24, 11, 18), (16, 37, 22), (32, 21, 22), (64, 4500, 22), (16, 5000, 22)])
+def test_hash_match_equals_hash_then_match(B, n_req, lg_slots):
     """Few requests (4 wavefronts each), thousands (1 wavefront each, 4 for the long ones), and a
-    block size that runs as two launches; half of the requests are indexed, a slice of their blocks evicted again."""
+    block size that runs as two launches; half of the requests are indexed, a slice of their blocks
+    evicted again (holes inside cached prefixes). Tables of 2^22 slots take the lookups of a tile
+    through the key words where the tile's last block is present."""
     rng = np.random.default_rng(B * 7 + n_req)
     tok, tok_off, lens = _ragged(rng, n_req, 0, 30 * B if n_req > 1000 else 150 * B)
     lens[1] = 0
@@ -531,7 +541,7 @@ def test_hash_match_equals_hash_then_match(B, n_req):
     blk_off = np.zeros(n_req + 1, dtype=np.int64)
     np.cumsum(lens // B, out=blk_off[1:])
     want_h = oracle.block_hash(tok, tok_off, blk_off, B, 11)
-    gi, oi = HipIndex(1 << 18), oracle.Index(1 << 18)
+    gi, oi = HipIndex(1 << lg_slots), oracle.Index(1 << lg_slots)
     cached = np.concatenate([want_h[blk_off[r]:blk_off[r + 1]] for r in range(0, n_req, 2)] + [want_h[:0]])
     cached = np.unique(cached)
     for ix in (gi, oi):
@@ -580,9 +590,10 @@ def test_route_parity(n_pods, num, den):
     assert want_hit.max() > 64
 
 
-@pytest.mark.parametrize("B,n_req,n_pods,num,den", [(16, 70, 7, 1, 2), (32, 41, 63, 1, 3), (64, 33, 5, 0, 1),
-                                                     (16, 4500, 8, 1, 2), (64, 4200, 3, 9, 10), (16, 9, 1, 2, 1)])
-def test_hash_match_route_equals_the_three_calls(B, n_req, n_pods, num, den):
+@pytest.mark.parametrize("B,n_req,n_pods,num,den,lg_slots", [
+    (16, 70, 7, 1, 2, 18), (32, 41, 63, 1, 3, 18), (64, 33, 5, 0, 1, 18), (16, 4500, 8, 1, 2, 18),
+    (64, 4200, 3, 9, 10, 18), (16, 9, 1, 2, 1, 18), (16, 70, 7, 1, 2, 22), (64, 4200, 3, 9, 10, 22)])
+def test_hash_match_route_equals_the_three_calls(B, n_req, n_pods, num, den, lg_slots):
     """Tokens in, pod out: the one-launch routing decision against the oracle's hash -> match ->
     route chain, on requests that share prefixes, with pods holding prefixes of every length
     (none, part of a tile, whole tiles, everything), zero-block requests, and both launch shapes
@@ -613,7 +624,7 @@ def test_hash_match_route_equals_the_three_calls(B, n_req, n_pods, num, den):
     per_key = np.zeros(len(uniq), dtype=np.uint64)
     np.bitwise_or.at(per_key, inv, sets)                               # a shared block is held by the union
     present = per_key != 0
-    gi, oi = HipIndex(1 << 18), oracle.Index(1 << 18)
+    gi, oi = HipIndex(1 << lg_slots), oracle.Index(1 << lg_slots)
     for ix in (gi, oi):
         ix.insert(uniq[present], per_key[present])
         ix.insert(rng.integers(1, 2**63, size=50000, dtype=np.uint64), np.full(50000, 1, dtype=np.uint64))
