@@ -48,9 +48,9 @@ struct Table {
 // Tables from this many slots on let lookup_tile guess: their tags (4 MiB and more) no longer stay in
 // an XCD's L2, so a key that is present costs a line of tags besides its slot's line, and every line
 // that leaves the L2 is 128 bytes at the rate of a streaming read. Measured with every key present:
-// lookups 32 % (2^22 slots at load 0.7) and 28 % (2^24 at 0.75) faster, 15-17 % in the kernel that also
-// hashes; with every key absent 7-17 % slower in the lookups alone (the one dependent read in front)
-// and 0-4 % in the hashing kernel. Smaller tables lose 24-28 % on absent keys and gain at most 5 %.
+// lookup time -24 % (2^22 slots at load 0.7 and 2^24 at 0.75), -13 % in the kernel that also hashes;
+// with every key absent +1...+10 % in the lookups alone (the one dependent read in front) and
+// +-2 % in the hashing kernel. Smaller tables lose 24-28 % on absent keys and gain at most 5 %.
 constexpr u64 kGuessPresentFrom = 1ull << 22;
 
 __device__ __forceinline__ u64 home_bucket(const Table& t, u64 key) {
