@@ -15,7 +15,7 @@ by the whole step's time. `roofline` is the gather kernel and `roofline_scatter`
 against 8 TB/s, each timed with HIP events inside the timed steps. `per_config` holds, for each of
 the five workloads: gather, scatter and two-stream bandwidth at its pool geometry, native-size call
 latencies, and the scaled hash+match batch (>= 4 Mi blocks) at three matched fractions, against the
-152 B/block (344 B at 64-token blocks) roofline and against the bytes actually moved, with a
+152 B/block (344 B at 64-token blocks) roofline and against the bytes the kernels ask for, with a
 random-read calibration on tables of the same size. `cpu_baseline` is the CPU oracle on a bounded
 sample of the headline workload, on one thread and on all cores.
 """
