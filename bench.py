@@ -39,11 +39,11 @@ NO_VALUE = np.uint64(0xFFFFFFFFFFFFFFFF)
 COPY_KERNEL = {"gather": "aibx::kv_copy_xcd_kernel<true, 256, false>",
                "scatter": "aibx::kv_copy_xcd_kernel<false, 256, false>"}
 
-# HBM bytes per gather launch of the headline workload from two rocprofv3 --pmc runs (FETCH_SIZE, then
-# WRITE_SIZE), each scaled by what the same counter reads for a plain elementwise kernel of known
-# size (--calibrate); valid only for the kernel source they were taken on.
+# HBM bytes per gather and per scatter launch of the headline workload from two rocprofv3 --pmc runs
+# (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for a plain elementwise
+# kernel of known size (--calibrate); valid only for the kernel source they were taken on.
 MEASURED_TRAFFIC = {"kvcopy_sha1": "f7993a4a54130c5281bdd6484a450703775ef58d", "config": 3,
-                    "bytes_per_launch": 42951863323}
+                    "bytes_per_launch": 42951863323, "scatter_bytes_per_launch": 42948998002}
 
 
 def _u64(t):
@@ -1038,6 +1038,7 @@ def main():
     roof_s = _roofline(step.scatter_bytes, scatter_ms, COPY_KERNEL["scatter"], blocks=step.n_scattered)
     if (MEASURED_TRAFFIC["kvcopy_sha1"] == _kvcopy_sha1() and MEASURED_TRAFFIC["config"] == args.config):
         roof_g["traffic"] = MEASURED_TRAFFIC["bytes_per_launch"]
+        roof_s["traffic"] = MEASURED_TRAFFIC["scatter_bytes_per_launch"]
     out = {
         "metric": "kv_gather_scatter_hbm_GBps", "value": value, "unit": "GB/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
