@@ -143,12 +143,6 @@ __device__ __forceinline__ u64 exchange_add(u64 a, u64 b, bool bit_set) {
   }
 }
 
-__device__ __forceinline__ u64 readlane64(u64 v, int lane) {
-  const u32 lo = (u32)__builtin_amdgcn_readlane((int)(u32)v, lane);
-  const u32 hi = (u32)__builtin_amdgcn_readlane((int)(u32)(v >> 32), lane);
-  return ((u64)hi << 32) | lo;
-}
-
 // ---- fast path: block sizes 16, 32, 64 -------------------------------------------------------
 // With kMatch the kernel also looks every hash up in the index as soon as it is formed (one lane
 // per block, the lane reads the whole bucket) and reduces the first miss of the request, so the

@@ -49,9 +49,17 @@ struct Table {
 // an XCD's L2, so a key that is present costs a line of tags besides its slot's line, and every line
 // that leaves the L2 is 128 bytes at the rate of a streaming read. Measured with every key present:
 // lookup time -24 % (2^22 slots at load 0.7 and 2^24 at 0.75), -13 % in the kernel that also hashes;
-// with every key absent +1...+10 % in the lookups alone (the one dependent read in front) and
-// +-2 % in the hashing kernel. Smaller tables lose 24-28 % on absent keys and gain at most 5 %.
+// with every key absent no difference beyond the run-to-run spread (the question is asked on the
+// scalar side: two readlanes, scalar multiplies, one 8-byte read). In smaller tables the tags are
+// cached, and going through the key words costs present keys 10 % (2^20 slots) to 40 % (2^12).
 constexpr u64 kGuessPresentFrom = 1ull << 22;
+
+// The value lane `lane` holds, in every lane (`lane` must be the same in all of them): a scalar.
+__device__ __forceinline__ u64 readlane64(u64 v, int lane) {
+  const u32 lo = (u32)__builtin_amdgcn_readlane((int)(u32)v, lane);
+  const u32 hi = (u32)__builtin_amdgcn_readlane((int)(u32)(v >> 32), lane);
+  return ((u64)hi << 32) | lo;
+}
 
 __device__ __forceinline__ u64 home_bucket(const Table& t, u64 key) {
   return t.shift >= 64 ? 0ull : (key * kHomeMul) >> t.shift;
@@ -224,7 +232,9 @@ __device__ __forceinline__ u64 lookup_tile(const Table& t, u64 key, bool valid, 
   bool in_keys = false;
   if (ask && live) {
     const int last = 63 - __clzll((unsigned long long)live);
-    const u64 k = __shfl(key, last);  // the tile's last key, the same in every lane
+    // the tile's last key as a scalar: its bucket, its tag, the read of its tags and their test
+    // then cost the vector unit nothing
+    const u64 k = readlane64(key, last);
     if (k != kEmpty && k != kTomb) {
       const u64 b = home_bucket(t, k);
       const u64 tags = *tag_word(t, b);
