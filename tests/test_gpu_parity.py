@@ -442,6 +442,44 @@ def test_index_load_095_on_a_million_slots_matches_the_oracle():
     assert np.array_equal(gi.counters_evict, oi.counters_evict)
 
 
+def test_key_word_search_walks_long_sequences_on_a_large_full_table():
+    """Tables of 2^22 slots take a tile's lookups through the key words when the tile's last key is
+    present. Here that guess holds for every tile while half of the other keys are absent, on a table
+    at load 0.95 with tombstones: absent keys walk many full buckets of their probe sequence in the
+    key words, present ones sit deep in theirs. Values and match lengths equal the oracle's."""
+    n_slots = 1 << 22
+    rng = np.random.default_rng(2295)
+    keys = np.unique(rng.integers(1, 2**63, size=int(1.2 * n_slots), dtype=np.uint64))
+    rng.shuffle(keys)
+    target = int(0.95 * n_slots)
+    present, absent = keys[:target], keys[target:]
+    gi, oi = HipIndex(n_slots), oracle.Index(n_slots)
+    for ix in (gi, oi):
+        ix.insert(present, present >> np.uint64(3))
+    gone = present[::16]
+    assert np.array_equal(gi.evict(gone), oi.evict(gone))               # tombstones in full buckets
+    back = gone[::2]
+    for ix in (gi, oi):
+        ix.insert(back, back + np.uint64(7))                             # half of them return, into tombstones
+    assert np.array_equal(gi.counters_insert, oi.counters_insert) and int(gi.counters_insert[2]) == 0
+    live = np.setdiff1d(present, gone[1::2])
+    sizes = rng.integers(1, 200, size=3000)
+    blk_off = np.zeros(len(sizes) + 1, dtype=np.int64)
+    np.cumsum(sizes, out=blk_off[1:])
+    n = int(blk_off[-1])
+    h = rng.choice(live, size=n)
+    holes = rng.random(n) < 0.5
+    h[holes] = rng.choice(np.concatenate([absent, gone[1::2]]), size=int(holes.sum()))
+    for r in range(len(sizes)):                                          # the last key of every tile of every request is present
+        ends = np.arange(blk_off[r] + 63, blk_off[r + 1], 64)
+        ends = np.append(ends, blk_off[r + 1] - 1)
+        h[ends] = rng.choice(live, size=len(ends))
+    gv, gm = gi.match(h, blk_off)
+    ov, om = oi.match(h, blk_off)
+    assert np.array_equal(gv, ov) and np.array_equal(gm, om)
+    assert (ov == NO).sum() > n // 3 and (ov != NO).sum() > n // 3
+
+
 def test_match_edge_cases():
     gi, oi = HipIndex(64), oracle.Index(64)
     keys = np.arange(1, 30, dtype=np.uint64)
