@@ -110,8 +110,9 @@ __device__ __forceinline__ void load_bucket_keys(const u64* bucket, u64 (&keys)[
 // product's top lg(n_buckets) bits, so up to 2^35 slots the tag is independent of it (keys that
 // meet in a bucket still differ in their tags); the probe step (bits 7 and up) does share bits
 // with the tag in tables of 2^18 buckets or more, which costs nothing: keys with equal tags in
-// one bucket are told apart by the key comparison, whatever their steps. The update kernels write a slot's tag after they have won its key word, so
-// between launches the tags mirror the keys exactly. A lookup walks the tags only - an eighth of
+// one bucket are told apart by the key comparison, whatever their steps. The update kernels write a
+// slot's tag after they have won its key word, so between launches the tags mirror the keys
+// exactly. A lookup walks the tags only - an eighth of
 // the bytes of the key words, so the tags of a table stay in cache where its slots do not (16 Mi
 // slots: 16 MiB of tags against 256 MiB of slots) - and touches a slot only where the tag matches:
 // always for a key that is present, with probability 1/254 per occupied slot for one that is not.
@@ -244,13 +245,6 @@ __device__ __forceinline__ u64 lookup_tile(const Table& t, u64 key, bool valid, 
   }
   if (in_keys) (void)find_slot_in_keys(t, key, valid, value);
   else (void)find_slot(t, key, valid, value);
-  return value;
-}
-
-// The key's value or kNoValue.
-__device__ __forceinline__ u64 lookup_one(const Table& t, u64 key, bool valid) {
-  u64 value = kNoValue;
-  (void)find_slot(t, key, valid, value);
   return value;
 }
 
