@@ -523,8 +523,10 @@ template <bool kMatch, bool kLengths, bool kRoute = false>
 int launch_hash(const int32_t* d_tokens, const int64_t* d_tok_off, const int64_t* d_blk_off, int32_t n_req,
                 int64_t n_blocks_total, int32_t block_size, u64 seed, u64* d_hash_out, MatchOut mo, hipStream_t st) {
   // Launch shape, from what the host knows (batch size and mean request length):
-  //  - fewer than 4,096 requests: four wavefronts per request, every request of more than one tile
-  //    shared by the four, so that a small batch finishes in few serial tiles;
+  //  - fewer than 4,096 requests: eight wavefronts per request, every request of more than one tile
+  //    shared by the eight, so that a small batch finishes in few serial tiles (1,024 lognormal
+  //    requests of up to 32,768 tokens, tokens -> values in one launch: 35 us with four wavefronts,
+  //    27 us with eight, 35 us with sixteen);
   //  - thousands of requests averaging under two tiles: one wavefront per request and nothing else
   //    (workgroups of four with three idle wavefronts cost +50 % on 100,000 one-tile requests);
   //  - thousands of longer requests: the GPU is full anyway, so a request of up to 8,192 tokens (4,096
@@ -537,7 +539,7 @@ int launch_hash(const int32_t* d_tokens, const int64_t* d_tok_off, const int64_t
   // decision) are wanted from a batch of thousands of requests, where everything a wavefront does
   // behind the first miss is wasted and a round of two wastes less (tokens -> lengths on 4 Mi-block
   // batches whose requests miss early: -12 % to -45 % against rounds of four). A small batch leaves
-  // most of the GPU idle, so there wasted work is free and the serial chain is what counts: four
+  // most of the GPU idle, so there wasted work is free and the serial chain is what counts: eight
   // wavefronts and full tiles in every form (128 requests of 16,384 tokens with every block present,
   // tokens -> pod: 26 us with rounds of two 1024-token tiles).
   constexpr int kShared = kLengths ? 2 : 4;
@@ -555,7 +557,7 @@ int launch_hash(const int32_t* d_tokens, const int64_t* d_tok_off, const int64_t
     block_hash_pow2_kernel<B, (kSubFew ? kSubFew : B / 16), 1, kMatch, kLengths, kRoute><<<grid, kWave, 0, st>>>( \
         d_tokens, d_tok_off, d_blk_off, n_req, lg_run, seed, d_hash_out, mo, 0);                               \
   else if (small_batch)                                                                                        \
-    block_hash_pow2_kernel<B, B / 16, 4, kMatch, kLengths, kRoute><<<grid, 4 * kWave, 0, st>>>(                \
+    block_hash_pow2_kernel<B, B / 16, 8, kMatch, kLengths, kRoute><<<grid, 8 * kWave, 0, st>>>(                \
         d_tokens, d_tok_off, d_blk_off, n_req, lg_run, seed, d_hash_out, mo, solo_tiles);                      \
   else                                                                                                         \
     block_hash_pow2_kernel<B, (kSubFew ? kSubFew : B / 16), kShared, kMatch, kLengths, kRoute>                 \

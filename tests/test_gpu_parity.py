@@ -560,7 +560,7 @@ def test_scan_does_not_push_out_reused_blocks_full_flow():
 @pytest.mark.parametrize("B,n_req,lg_slots", [(16, 37, 18), (32, 21, 18), (64, 19, 18), (16, 5000, 18), (64, 4500, 18),
                                               (24, 11, 18), (16, 37, 22), (32, 21, 22), (64, 4500, 22), (16, 5000, 22)])
 def test_hash_match_equals_hash_then_match(B, n_req, lg_slots):
-    """Few requests (4 wavefronts each), thousands (1 wavefront each, 4 for the long ones), and a
+    """Few requests (8 wavefronts each), thousands (1 wavefront each, 4 for the long ones), and a
     block size that runs as two launches; half of the requests are indexed, a slice of their blocks
     evicted again (holes inside cached prefixes). Tables of 2^22 slots take the lookups of a tile
     through the key words where the tile's last block is present."""
@@ -568,7 +568,7 @@ def test_hash_match_equals_hash_then_match(B, n_req, lg_slots):
     tok, tok_off, lens = _ragged(rng, n_req, 0, 30 * B if n_req > 1000 else 150 * B)
     lens[1] = 0
     lens[2] = B - 1
-    # requests long enough to take several rounds of four wavefronts, in large and small batches
+    # requests long enough to take several rounds of their workgroup's wavefronts, in large and small batches
     lens[6], lens[7], lens[8] = 8192 + 3 * B, 8192 + 3 * B + 40, 21 * 1024 + 7
     np.cumsum(lens, out=tok_off[1:])
     tok = rng.integers(0, 32000, size=int(tok_off[-1]), dtype=np.int32)
