@@ -92,17 +92,6 @@ __device__ __forceinline__ u64 chain_scan(u64 d, int lane) {
   return d;
 }
 
-// 64-bit value through a DPP lane pattern (a VALU operand modifier: no LDS round trip). Lanes
-// whose source is outside the row read 0.
-template <int kCtrl>
-__device__ __forceinline__ u64 dpp64(u64 v) {
-  const u32 lo = (u32)__builtin_amdgcn_update_dpp(0, (int)(u32)v, kCtrl, 0xF, 0xF, true);
-  const u32 hi = (u32)__builtin_amdgcn_update_dpp(0, (int)(u32)(v >> 32), kCtrl, 0xF, 0xF, true);
-  return ((u64)hi << 32) | lo;
-}
-constexpr int kDppRowMirror = 0x140, kDppRowHalfMirror = 0x141, kDppQuadReverse = 0x1B, kDppQuadSwap = 0xB1;
-constexpr int kDppRowShr = 0x110;  // + shift (1..15)
-
 // Value of the butterfly partner across lane bit kMask. Any partner on the other side of that bit
 // will do as long as later levels stay inside the halves this level made, so inside a row of 16
 // lanes the mirror patterns serve (15-i, 7-i, 3-i, i^1); across rows it takes a bpermute.
@@ -367,11 +356,7 @@ __global__ __launch_bounds__(kHashWaves* kWave)
     if constexpr (kRoute) {
       u64 v = lookup_tile(mo.table, h, valid, ask);
       v = valid ? (v == kNoValue ? 0ull : (v & all_pods)) : all_pods;  // lanes past the end do not shrink the set
-#pragma unroll
-      for (int o = 1; o < kWave; o <<= 1) {  // inclusive AND scan over the tile's blocks
-        const u64 up = shfl_up64(v, o);
-        if (lane >= o) v &= up;
-      }
+      v = and_scan64(v, lane);  // over the tile's blocks
       const u64 tile_set = readlane64(v, kWave - 1);
       u64 before = alive;  // pods holding every block before this wavefront's tile
       if (!solo) {

@@ -4,6 +4,7 @@
 #pragma once
 
 #include "common.h"
+#include "wave_ops.h"
 
 struct aibx_index {
   aibx::u64* slots;       // device, 2*n_slots words: buckets of 8 keys followed by their 8 values
@@ -53,13 +54,6 @@ struct Table {
 // scalar side: two readlanes, scalar multiplies, one 8-byte read). In smaller tables the tags are
 // cached, and going through the key words costs present keys 10 % (2^20 slots) to 40 % (2^12).
 constexpr u64 kGuessPresentFrom = 1ull << 22;
-
-// The value lane `lane` holds, in every lane (`lane` must be the same in all of them): a scalar.
-__device__ __forceinline__ u64 readlane64(u64 v, int lane) {
-  const u32 lo = (u32)__builtin_amdgcn_readlane((int)(u32)v, lane);
-  const u32 hi = (u32)__builtin_amdgcn_readlane((int)(u32)(v >> 32), lane);
-  return ((u64)hi << 32) | lo;
-}
 
 __device__ __forceinline__ u64 home_bucket(const Table& t, u64 key) {
   return t.shift >= 64 ? 0ull : (key * kHomeMul) >> t.shift;

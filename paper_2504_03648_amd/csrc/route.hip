@@ -6,24 +6,21 @@
 // The set of pods that hold ALL of blocks 0..j is the running AND of those sets; it only shrinks,
 // so the longest prefix any pod holds ends where the running AND becomes empty, and the pods that
 // hold that longest prefix are the last non-empty running AND. No per-pod loop is needed: the
-// wavefront scans 64 blocks per trip with a cross-lane AND scan and stops at the first empty set.
+// wavefront scans 64 blocks per trip with a cross-lane AND scan (DPP row shifts and three scalar
+// reads, no LDS) and stops at the first empty set.
 #include "common.h"
+#include "wave_ops.h"
 
 namespace aibx {
 namespace {
 
 constexpr u64 kNoValue = AIBX_NO_VALUE;
 
-__device__ __forceinline__ u64 shfl_up64(u64 v, int d) {
+// The value of lane `src`, which may differ from lane to lane (through the LDS crossbar).
+__device__ __forceinline__ u64 shfl64(u64 v, int src) {
   u32 lo = (u32)v, hi = (u32)(v >> 32);
-  lo = __shfl_up(lo, d);
-  hi = __shfl_up(hi, d);
-  return ((u64)hi << 32) | lo;
-}
-__device__ __forceinline__ u64 readlane64(u64 v, int lane) {
-  u32 lo = (u32)v, hi = (u32)(v >> 32);
-  lo = __shfl(lo, lane);
-  hi = __shfl(hi, lane);
+  lo = __shfl(lo, src);
+  hi = __shfl(hi, src);
   return ((u64)hi << 32) | lo;
 }
 
@@ -43,7 +40,7 @@ __global__ __launch_bounds__(kWave) void route_kernel(const u64* __restrict__ po
   u64 best_rank = my_rank;
 #pragma unroll
   for (int m = 32; m >= 1; m >>= 1) {
-    const u64 o = readlane64(best_rank, lane ^ m);
+    const u64 o = shfl64(best_rank, lane ^ m);
     best_rank = o < best_rank ? o : best_rank;
   }
   const int fallback_pod = (int)(best_rank & 0xFF);
@@ -52,17 +49,16 @@ __global__ __launch_bounds__(kWave) void route_kernel(const u64* __restrict__ po
   int64_t best_len = 0;      // longest prefix held by any pod
   u64 best_set = 0;          // the pods holding it
   int64_t fallback_len = 0;  // prefix held by the fallback pod
+  // the next tile's sets are requested while this tile is scanned
+  u64 v_next = lane < n_r ? pod_sets[b0 + lane] : all_pods;
   for (int64_t base = 0; base < n_r && alive != 0; base += kWave) {
     const bool valid = base + lane < n_r;
-    u64 v = valid ? pod_sets[b0 + base + lane] : all_pods;  // lanes past the end do not shrink the set
+    u64 v = v_next;
+    v_next = base + kWave + lane < n_r ? pod_sets[b0 + base + kWave + lane] : all_pods;
     v = v == kNoValue ? 0ull : (v & all_pods);
-    if (!valid) v = all_pods;
+    if (!valid) v = all_pods;  // lanes past the end do not shrink the set
     // inclusive AND scan across lanes, then the sets carried in from earlier tiles
-#pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) {
-      const u64 up = shfl_up64(v, o);
-      if (lane >= o) v &= up;
-    }
+    v = and_scan64(v, lane);
     v &= alive;
     const u64 nonempty = __ballot(valid && v != 0);            // a run of ones from lane 0
     const u64 has_fb = __ballot(valid && ((v >> fallback_pod) & 1ull));
@@ -80,7 +76,7 @@ __global__ __launch_bounds__(kWave) void route_kernel(const u64* __restrict__ po
   if (aware && !((best_set >> lane) & 1ull)) rank = ~0ull;  // candidates: the pods of best_set
 #pragma unroll
   for (int m = 32; m >= 1; m >>= 1) {
-    const u64 o = readlane64(rank, lane ^ m);
+    const u64 o = shfl64(rank, lane ^ m);
     rank = o < rank ? o : rank;
   }
   if (lane == 0) {
