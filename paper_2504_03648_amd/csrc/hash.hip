@@ -224,13 +224,7 @@ __global__ __launch_bounds__(kHashWaves* kWave)
   if constexpr (kRoute) {
     all_pods = (1ull << mo.n_pods) - 1ull;  // n_pods <= 63
     if (lane < mo.n_pods) my_rank = ((u64)(u32)mo.pod_load[lane] << 8) | (u64)lane;
-    u64 best_rank = my_rank;
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) {
-      const u64 o = shfl_xor64(best_rank, m);
-      best_rank = o < best_rank ? o : best_rank;
-    }
-    fallback_pod = (int)(best_rank & 0xFF);
+    fallback_pod = (int)(wave_min64(my_rank) & 0xFF);
   }
   if (n_r <= 0) {
     if constexpr (kRoute) {
@@ -430,11 +424,7 @@ __global__ __launch_bounds__(kHashWaves* kWave)
     const bool aware = best_len > 0 && (u64)best_len * mo.thr_den >= mo.thr_num * (u64)n_r;
     u64 rank = my_rank;
     if (aware && !((last_set >> lane) & 1ull)) rank = ~0ull;  // candidates: the holders of the longest prefix
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) {
-      const u64 o = shfl_xor64(rank, m);
-      rank = o < rank ? o : rank;
-    }
+    rank = wave_min64(rank);
     if (lane == 0) {
       mo.pod_out[r] = (int32_t)(rank & 0xFF);
       mo.hit_len_out[r] = (int32_t)(aware ? best_len : n_fallback);

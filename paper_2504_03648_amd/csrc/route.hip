@@ -16,13 +16,6 @@ namespace {
 
 constexpr u64 kNoValue = AIBX_NO_VALUE;
 
-// The value of lane `src`, which may differ from lane to lane (through the LDS crossbar).
-__device__ __forceinline__ u64 shfl64(u64 v, int src) {
-  u32 lo = (u32)v, hi = (u32)(v >> 32);
-  lo = __shfl(lo, src);
-  hi = __shfl(hi, src);
-  return ((u64)hi << 32) | lo;
-}
 
 __global__ __launch_bounds__(kWave) void route_kernel(const u64* __restrict__ pod_sets,
                                                       const int64_t* __restrict__ blk_off, int n_pods,
@@ -37,13 +30,7 @@ __global__ __launch_bounds__(kWave) void route_kernel(const u64* __restrict__ po
 
   // least-request pod over all pods (the fallback), ties to the lower id: min of (load, id)
   const u64 my_rank = lane < n_pods ? ((u64)(u32)pod_load[lane] << 8) | (u64)lane : ~0ull;
-  u64 best_rank = my_rank;
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) {
-    const u64 o = shfl64(best_rank, lane ^ m);
-    best_rank = o < best_rank ? o : best_rank;
-  }
-  const int fallback_pod = (int)(best_rank & 0xFF);
+  const int fallback_pod = (int)(wave_min64(my_rank) & 0xFF);
 
   u64 alive = all_pods;      // pods holding every block seen so far
   int64_t best_len = 0;      // longest prefix held by any pod
@@ -74,11 +61,7 @@ __global__ __launch_bounds__(kWave) void route_kernel(const u64* __restrict__ po
   const bool aware = n_r > 0 && best_len > 0 && (u64)best_len * thr_den >= thr_num * (u64)n_r;
   u64 rank = my_rank;
   if (aware && !((best_set >> lane) & 1ull)) rank = ~0ull;  // candidates: the pods of best_set
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) {
-    const u64 o = shfl64(rank, lane ^ m);
-    rank = o < rank ? o : rank;
-  }
+  rank = wave_min64(rank);
   if (lane == 0) {
     pod_out[r] = (int32_t)(rank & 0xFF);
     hit_len_out[r] = (int32_t)(aware ? best_len : fallback_len);

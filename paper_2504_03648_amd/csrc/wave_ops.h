@@ -25,6 +25,27 @@ __device__ __forceinline__ u64 dpp64(u64 v) {
 constexpr int kDppRowMirror = 0x140, kDppRowHalfMirror = 0x141, kDppQuadReverse = 0x1B, kDppQuadSwap = 0xB1;
 constexpr int kDppRowShr = 0x110;  // + shift (1..15)
 
+// Like dpp64, but lanes whose source is outside the row keep their own value.
+template <int kCtrl>
+__device__ __forceinline__ u64 dpp64_or_self(u64 v) {
+  const u32 lo = (u32)__builtin_amdgcn_update_dpp((int)(u32)v, (int)(u32)v, kCtrl, 0xF, 0xF, false);
+  const u32 hi = (u32)__builtin_amdgcn_update_dpp((int)(u32)(v >> 32), (int)(u32)(v >> 32), kCtrl, 0xF, 0xF, false);
+  return ((u64)hi << 32) | lo;
+}
+
+// Minimum over the 64 lanes, the same scalar in every lane: a running minimum along each row of 16
+// lanes (four DPP row shifts), then the rows' last lanes.
+__device__ __forceinline__ u64 wave_min64(u64 v) {
+  u64 o;
+  o = dpp64_or_self<kDppRowShr + 1>(v); v = o < v ? o : v;
+  o = dpp64_or_self<kDppRowShr + 2>(v); v = o < v ? o : v;
+  o = dpp64_or_self<kDppRowShr + 4>(v); v = o < v ? o : v;
+  o = dpp64_or_self<kDppRowShr + 8>(v); v = o < v ? o : v;
+  const u64 a = readlane64(v, 15), b = readlane64(v, 31), c = readlane64(v, 47), d = readlane64(v, 63);
+  const u64 ab = a < b ? a : b, cd = c < d ? c : d;
+  return ab < cd ? ab : cd;
+}
+
 // Inclusive AND scan over the 64 lanes: lane l gets v_0 & v_1 & ... & v_l. Inside a row of 16 lanes
 // four DPP row shifts on the complement (a shift feeds zeros into the row's first lanes, and zero is
 // the identity of OR); across rows three scalar reads of the rows' last lanes. No LDS traffic, where
