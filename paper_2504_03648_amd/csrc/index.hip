@@ -350,10 +350,14 @@ __global__ __launch_bounds__(kIndexThreads) void index_count_kernel(const u64* s
 }
 
 // Dump and victim selection: emit the (key, value) pairs of the slots that pass a test, in no
-// particular order. Every workgroup owns one contiguous stretch of the table and goes over it
-// twice: first it counts its matches and reserves that many output positions with ONE atomic (an
+// particular order. Every workgroup owns one contiguous stretch of the table, every wavefront a
+// quarter of it, and goes over it twice: first it counts its matches (a ballot per 64 slots, so the
+// count is a scalar) and the workgroup reserves that many output positions with ONE atomic (an
 // atomic per wavefront on the shared counter serialises at ~13 ns each and made a scan of a
-// 16 M-slot table take 3 ms), then it re-reads the stretch - mostly from cache - and writes.
+// 16 M-slot table take 3 ms); then every wavefront re-reads its quarter - mostly from cache - and
+// writes its matches behind those of the wavefronts before it. Two barriers per workgroup, none
+// per tile.
+constexpr int kEmitBatch = 4;
 struct EmitTest {
   bool victims;        // false: every live key; true: live, count < protect_count, last < before_epoch
   u32 protect_count, before_epoch;
@@ -372,42 +376,58 @@ __global__ __launch_bounds__(kIndexThreads) void index_emit_kernel(const u64* sl
   __shared__ u32 lds_wave[kWavesPerGroup];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   u64 chunk = (n_slots + gridDim.x - 1) / gridDim.x;
-  chunk = (chunk + kIndexThreads - 1) / kIndexThreads * kIndexThreads;
-  const u64 begin = (u64)blockIdx.x * chunk;
-  const u64 end = begin + chunk < n_slots ? begin + chunk : n_slots;
-  u32 mine = 0;
-  for (u64 i = begin + threadIdx.x; i < end; i += kIndexThreads)
-    mine += emit_passes(test, slots[key_word_of_slot(i)], test.victims ? usage[i] : 0u);
-  const u32 total = group_sum(mine);  // valid in thread 0
-  if (threadIdx.x == 0) lds_base = total ? atomicAdd((unsigned long long*)n_out, (unsigned long long)total) : 0ull;
+  chunk = (chunk + kIndexThreads - 1) / kIndexThreads * kIndexThreads;  // a multiple of 64 per wavefront
+  const u64 part = chunk / kWavesPerGroup;
+  const u64 begin = (u64)blockIdx.x * chunk + (u64)wave * part;       // this wavefront's slots
+  const u64 end = begin + part < n_slots ? begin + part : n_slots;
+  // kEmitBatch tiles of 64 slots per trip, all their loads requested before the first is used: one
+  // memory latency per trip instead of one (two with the value behind the test) per tile
+  u32 mine = 0;  // the same in every lane of the wavefront
+  for (u64 tile = begin; tile < end; tile += kEmitBatch * kWave) {
+    u64 k[kEmitBatch];
+    u32 u[kEmitBatch];
+#pragma unroll
+    for (int j = 0; j < kEmitBatch; ++j) {
+      const u64 i = tile + (u64)j * kWave + lane;
+      k[j] = i < end ? slots[key_word_of_slot(i)] : kEmpty;
+      u[j] = (i < end && test.victims) ? usage[i] : 0u;
+    }
+#pragma unroll
+    for (int j = 0; j < kEmitBatch; ++j) mine += (u32)__popcll(__ballot(emit_passes(test, k[j], u[j])));
+  }
+  if (lane == 0) lds_wave[wave] = mine;
   __syncthreads();
-  u64 pos0 = lds_base;  // next free output position of this workgroup
-  for (u64 tile = begin; tile < end; tile += kIndexThreads) {  // same trip count for every thread
-    const u64 i = tile + threadIdx.x;
-    u64 k = kEmpty, v = 0;
-    bool pass = false;
-    if (i < end) {
-      k = slots[key_word_of_slot(i)];
-      pass = emit_passes(test, k, test.victims ? usage[i] : 0u);
-      if (pass) v = slots[key_word_of_slot(i) + kBucket];
+  if (threadIdx.x == 0) {
+    u32 total = 0;
+    for (int w = 0; w < kWavesPerGroup; ++w) total += lds_wave[w];
+    lds_base = total ? atomicAdd((unsigned long long*)n_out, (unsigned long long)total) : 0ull;
+  }
+  __syncthreads();
+  u64 pos0 = lds_base;  // next free output position of this wavefront
+  for (int w = 0; w < wave; ++w) pos0 += lds_wave[w];
+  for (u64 tile = begin; tile < end; tile += kEmitBatch * kWave) {
+    u64 k[kEmitBatch], v[kEmitBatch];
+    u32 u[kEmitBatch];
+#pragma unroll
+    for (int j = 0; j < kEmitBatch; ++j) {  // the value comes with its key: same 128-byte line
+      const u64 i = tile + (u64)j * kWave + lane;
+      k[j] = i < end ? slots[key_word_of_slot(i)] : kEmpty;
+      v[j] = i < end ? slots[key_word_of_slot(i) + kBucket] : 0ull;
+      u[j] = (i < end && test.victims) ? usage[i] : 0u;
     }
-    const u64 mask = __ballot(pass);
-    if (lane == 0) lds_wave[wave] = (u32)__popcll(mask);
-    __syncthreads();
-    u32 before = 0, all = 0;
-    for (int w = 0; w < kWavesPerGroup; ++w) {
-      before += w < wave ? lds_wave[w] : 0u;
-      all += lds_wave[w];
-    }
-    if (pass) {
-      const u64 pos = pos0 + before + __popcll(mask & ((1ull << lane) - 1ull));
-      if (pos < capacity) {
-        keys_out[pos] = k;
-        values_out[pos] = v;
+#pragma unroll
+    for (int j = 0; j < kEmitBatch; ++j) {
+      const bool pass = emit_passes(test, k[j], u[j]);
+      const u64 mask = __ballot(pass);
+      if (pass) {
+        const u64 pos = pos0 + __popcll(mask & ((1ull << lane) - 1ull));
+        if (pos < capacity) {
+          keys_out[pos] = k[j];
+          values_out[pos] = v[j];
+        }
       }
+      pos0 += __popcll(mask);
     }
-    pos0 += all;
-    __syncthreads();  // lds_wave is rewritten by the next tile
   }
 }
 
