@@ -275,13 +275,18 @@ __global__ __launch_bounds__(kHashWaves* kWave)
           p[k] = y ^ (y >> 32);
         }
       } else {
+        // the request's full blocks end inside this sub-step: rows of 64 tokens that lie wholly before
+        // that end are read like any other, the row the end falls in lane by lane, the rest not at all
+        // (the row counts are the same in every lane, so only one row pays for a comparison)
+        const int full_rows = (int)((n_tok - sbase) / kWave), rest = (int)((n_tok - sbase) % kWave);
 #pragma unroll
         for (int k = 0; k < kLoads; ++k) {
-          const int64_t idx = sbase + k * kWave + lane;
-          raw[k] = idx < n_tok ? __builtin_nontemporal_load(tok + idx) : 0;
+          raw[k] = 0;
+          if (k < full_rows) raw[k] = __builtin_nontemporal_load(tok + sbase + k * kWave + lane);
+          else if (k == full_rows && lane < rest) raw[k] = __builtin_nontemporal_load(tok + sbase + k * kWave + lane);
         }
         // loads that lie behind the request's last full block altogether skip their arithmetic
-        const int live = (int)((n_tok - sbase + kWave - 1) / kWave);
+        const int live = full_rows + (rest != 0);
 #pragma unroll
         for (int k = 0; k < kLoads; ++k) {
           p[k] = 0;
